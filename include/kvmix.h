@@ -1,0 +1,169 @@
+/*
+ * kvmix.h — C-ABI boundary of the KVmix hot path on MI355X (gfx950).
+ *
+ * The library implements the two data-parallel parts of KVmix (arXiv 2506.08018):
+ *   part 1  group-wise asymmetric min/max quantization of the KV cache at a layer's own
+ *           Key / Value bit-width, with bit-packing into 32-bit words (paper Sec. 3.2.1,
+ *           3.2.2 incl. the unnumbered q_max equation for the 3-bit "10 x 3 bit + 1 x 2 bit"
+ *           block), applied to tokens that leave the full-precision recent window
+ *           (Recent Pivotal Context, Sec. 3.3, Fig. 4); and
+ *   part 2  decode attention that dequantizes the packed codes on the fly while it
+ *           multiplies ("fusion of dequantization and matrix-vector multiplication",
+ *           Sec. 3.4 item 2), over [packed old tokens || fp16 recent window].
+ * The per-layer bit table (Sec. 3.1, Sec. 4.2) is an input.
+ *
+ * Conventions
+ *   - plain C, every pointer is DEVICE memory unless marked "host"; structs are host memory.
+ *   - fp16 values travel as uint16_t bit patterns (IEEE binary16).
+ *   - every entry point returns 0 (KVMIX_OK) or a negative kvmix_status; arguments are
+ *     validated on the host before anything is launched: a failing call launches nothing
+ *     and writes nothing.
+ *   - the caller owns every buffer; the library allocates nothing and keeps no state
+ *     besides the last HIP error code. Work is enqueued on `stream` (a hipStream_t passed
+ *     as void*, NULL = default stream) and the call returns without synchronizing.
+ *   - one "unit" is one (batch b, kv head j) pair, u = b*Hkv + j. Query head h reads kv head
+ *     h / G, G = Hq / Hkv (G in {1,2,4,8}).
+ *   - D = 128 and group = 32 are the only supported head dimension / group size
+ *     (the paper's setting, Sec. 4.2).
+ *
+ * Packed cache layout (per layer; all arrays unit-major, then 32-token tile-major)
+ *   A "tile" is 32 consecutive tokens x 128 channels of one unit. Token index inside the tile
+ *   tau = 0..31, channel d = 0..127.
+ *   Keys are quantized per channel: a group is the 32 tokens of a tile for one channel
+ *   (Sec. 3.2.1: tensor viewed as [B*nh*D, T], cut into groups of 32 along T).
+ *   Values are quantized per token: a group is 32 consecutive channels of one token, g = d/32.
+ *   k_scale/k_zero : [units][T_cap/32][128] fp16   (scale s and group minimum per channel)
+ *   v_scale/v_zero : [units][T_cap/32][4][32] fp16  (index [g][tau] inside the tile)
+ *   k_codes/v_codes: [units][T_cap/32][128*bits] uint32 words; the bit position of every code
+ *   inside its tile is given below. "lane" l = 0..63 names the 16-byte column of a 1 KiB
+ *   block, l = 16*kq + i.
+ *     Key code (tau, d):   ks = d/32, kq = (d%32)/8, j = (d%8)/2, hh = d%2,
+ *                          m = (tau%8)/4, i = 4*(tau/8) + tau%4
+ *     Value code (tau, d): kq = tau/8, j = (tau%8)/2, hh = tau%2, m = d/16 (0..7), i = d%16
+ *     2-bit: word 4*l + j, bits [16*hh + 2*f, +2), f = ks + 4*m (Key) or f = m (Value).
+ *     4-bit: word 256*c + 4*l + j, bits [16*hh + 4*f, +4),
+ *            Key: c = ks/2, f = ks%2 + 2*m;  Value: c = m/4, f = m%4.
+ *     3-bit: code = lo + 4*hi. The 2-bit plane `lo` is stored exactly like a 2-bit tile
+ *            (256 words), followed by the 1-bit plane `hi` (128 words): word 256 + 2*l + j/2,
+ *            bit 16*hh + 8*(j%2) + beta, beta = 2*ks + m (Key) or 2*(m%4) + m/4 (Value).
+ *            The two elements of every group that the paper stores with 2 bits (in-group
+ *            index 10 and 21: the 11th element of the first and second block of 11) have
+ *            hi = 0 by construction, so a group occupies 3 words = 30*3 + 2*2 + 2 unused bits,
+ *            the density of the paper's 11-per-word packing.
+ *   Unused bits are zero.
+ *
+ * Recent window (fp16, ring buffer of W_cap slots, W_cap % 32 == 0, W_cap >= window + 32)
+ *   k_win : [units][W_cap][128]   (channel contiguous)
+ *   v_win : [units][128][W_cap]   (slot contiguous: the Value window is stored transposed)
+ *   The n_w valid tokens sit in slots (w0 + r) % W_cap, r = 0..n_w-1, oldest first;
+ *   w0 % 32 == 0. Both windows must hold finite values in every slot (zero-fill at allocation).
+ */
+#ifndef KVMIX_H_
+#define KVMIX_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  KVMIX_OK = 0,
+  KVMIX_ERR_NULL = -1,      /* a required pointer is NULL */
+  KVMIX_ERR_BAD_BITS = -2,  /* bits not in {2,3,4}, or 16 for one of K/V only */
+  KVMIX_ERR_BAD_GROUP = -3, /* group != 32 */
+  KVMIX_ERR_BAD_SHAPE = -4, /* D != 128, Hq % Hkv, G not in {1,2,4,8}, counts not multiples of 32, capacity exceeded */
+  KVMIX_ERR_ALIGN = -5,     /* a pointer is not 16-byte aligned or a stride is not a multiple of 8 elements */
+  KVMIX_ERR_WORKSPACE = -6, /* workspace too small */
+  KVMIX_ERR_HIP = -7        /* a HIP call failed; see kvmix_last_hip_error() */
+} kvmix_status;
+
+/* Cache geometry of one layer (Sec. 3.2.1: cache shape [B, nh, T, D]). */
+typedef struct {
+  int32_t B;     /* batch */
+  int32_t Hq;    /* query heads */
+  int32_t Hkv;   /* key/value heads */
+  int32_t D;     /* head dimension, must be 128 */
+  int32_t group; /* quantization group size, must be 32 (Sec. 4.2) */
+} kvmix_shape;
+
+/* One row of the per-layer bit table (Sec. 3.1 step 3, Sec. 4.2) plus the window length. */
+typedef struct {
+  int32_t k_bits; /* 2, 3, 4, or 16 (= keep the whole layer in the fp16 window) */
+  int32_t v_bits; /* same set; 16 only together with k_bits == 16 */
+  int32_t window; /* number of most recent tokens kept in fp16 (the RPC count), multiple of 32 */
+} kvmix_layer_cfg;
+
+/* One layer's cache: caller-owned device buffers, host-side counters. */
+typedef struct {
+  uint32_t* k_codes; uint16_t* k_scale; uint16_t* k_zero;
+  uint32_t* v_codes; uint16_t* v_scale; uint16_t* v_zero;
+  uint16_t* k_win;   uint16_t* v_win;
+  int32_t T_cap; /* capacity of the packed part in tokens, multiple of 32 */
+  int32_t W_cap; /* window slots, multiple of 32, >= window + 32 */
+  int32_t n_q;   /* packed tokens (multiple of 32), the oldest n_q tokens of the sequence */
+  int32_t n_w;   /* valid window tokens */
+  int32_t w0;    /* ring start slot (multiple of 32) */
+} kvmix_layer_cache;
+
+int kvmix_version(void);
+const char* kvmix_strerror(int status);
+/* HIP error code (hipError_t as int) of the most recent KVMIX_ERR_HIP on this thread's process. */
+int kvmix_last_hip_error(void);
+
+/* Byte sizes of the eight cache arrays for capacities (T_cap, W_cap). Any output pointer may
+ * be NULL. k/v_meta_b is the size of EACH of scale and zero; win_b of EACH of k_win, v_win. */
+int kvmix_cache_bytes(const kvmix_shape* shape, const kvmix_layer_cfg* cfg, int T_cap, int W_cap,
+                      size_t* k_code_b, size_t* k_meta_b, size_t* v_code_b, size_t* v_meta_b,
+                      size_t* win_b);
+
+/* Workspace needed by kvmix_decode_attn for any context up to T_max packed tokens (split
+ * partials + arrival counters). The workspace must be zero-filled once before first use;
+ * every call leaves the counters zero again. */
+int kvmix_workspace_bytes(const kvmix_shape* shape, int T_max, size_t* bytes);
+
+/* Part 1 (Sec. 3.2.2 steps 1-4, Sec. 3.4 item 1). Quantize n_tokens (multiple of 32) fp16
+ * tokens of K and V and write codes/scales/zeros into the packed cache at token offset t0
+ * (multiple of 32, t0 + n_tokens <= T_cap). Element (b, j, t, d) of k_fp16 / v_fp16 is at
+ * index b*batch_stride + j*head_stride + t*token_stride + d (strides in elements, multiples
+ * of 8). Per group: mn/mx by fp16 comparison; s = fp16((mx - mn) / qmax) with fp32
+ * arithmetic; code = clamp(rint((x - mn) / s_i), 0, qmax_i) in fp32 with round-half-even,
+ * where for 3 bit the in-group elements 10 and 21 use qmax_i = 3 and s_i = (s*7)/3;
+ * a zero scale gives all-zero codes; the stored zero-point is mn (-0 stored as +0).
+ * Does not touch n_q / n_w (the caller sets cache->n_q). Inputs must be finite. */
+int kvmix_quantize_pack(const kvmix_shape* shape, const kvmix_layer_cfg* cfg,
+                        const uint16_t* k_fp16, const uint16_t* v_fp16,
+                        int64_t token_stride, int64_t head_stride, int64_t batch_stride,
+                        int n_tokens, int t0, const kvmix_layer_cache* cache, void* stream);
+
+/* Decode-time append of one token per sequence (Sec. 3.3, Fig. 4; Sec. 3.4 item 1):
+ * k_new, v_new are fp16 [B][Hkv][128]. The token goes into the next window slot; when the
+ * window then holds window + 32 tokens, the oldest 32 are quantized exactly as in
+ * kvmix_quantize_pack and written at token offset n_q of the packed cache ("concatenation"
+ * is an offset write into the pre-allocated cache). Updates n_q, n_w, w0 in *cache (host).
+ * With k_bits == 16 nothing is ever flushed (W_cap must hold the whole sequence). */
+int kvmix_append(const kvmix_shape* shape, const kvmix_layer_cfg* cfg,
+                 const uint16_t* k_new, const uint16_t* v_new,
+                 kvmix_layer_cache* cache, void* stream);
+
+/* Part 2 (Sec. 3.4 item 2; Sec. 3.2.2 dequantization x = q*s + min). For every query head h:
+ *   a_t  = softmax_scale * sum_d q[h][d] * Kt[t][d]           over all n_q + n_w tokens,
+ *   out  = sum_t softmax(a)_t * Vt[t][:]                       (no mask: one decode query)
+ * where Kt, Vt are the dequantized packed tokens followed by the fp16 window tokens.
+ * q, out: fp16 [B][Hq][128]. softmax_scale <= 0 selects 1/sqrt(D). Accumulation is fp32.
+ * n_splits: number of context splits per unit (split-K), 0 = chosen by the library.
+ * workspace: see kvmix_workspace_bytes (may be NULL when the effective n_splits is 1). */
+int kvmix_decode_attn(const kvmix_shape* shape, const kvmix_layer_cfg* cfg, const uint16_t* q,
+                      const kvmix_layer_cache* cache, float softmax_scale, uint16_t* out,
+                      void* workspace, size_t workspace_bytes, int n_splits, void* stream);
+
+/* Test helper: dequantize the n_q packed tokens back to fp32 (x = code*s_i + mn evaluated in
+ * fp32), which = 0 for K, 1 for V; out is [units][n_q][128]. */
+int kvmix_dequant(const kvmix_shape* shape, const kvmix_layer_cfg* cfg,
+                  const kvmix_layer_cache* cache, int which, float* out, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVMIX_H_ */

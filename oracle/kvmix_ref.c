@@ -1,0 +1,369 @@
+/*
+ * kvmix_ref.c — CPU oracle for the KVmix hot path (arXiv 2506.08018).
+ *
+ * TEST INFRASTRUCTURE ONLY. Plain, slow, written from the paper; it shares no code, header,
+ * table or helper with the HIP library and is only used by the tests, the smoke check and the
+ * benchmark's cpu_baseline leg. Nothing in the product path may call it.
+ *
+ * What it computes
+ *   - the group-wise asymmetric quantizer of Sec. 3.2.2 (steps 1-4 and the q_max case
+ *     equation for 3-bit blocks of 11), with Keys grouped per channel and Values per token
+ *     (Sec. 3.2.1), group size 32 (Sec. 4.2);
+ *   - the packed-cache encoding (bit positions documented in pos_key / pos_value below);
+ *   - decode attention by its plain definition: softmax(scale * q K~^T) V~ in fp64, where
+ *     K~, V~ are the dequantized packed tokens (x = q*s + min, Sec. 3.2.2 step 4) followed by
+ *     the fp16 recent window (Sec. 3.3). The fused kernel of Sec. 3.4 item 2 reaches exactly
+ *     this result; the fusion introduces no approximation.
+ *
+ * Readings of the paper where it is silent (each one is listed in the design document):
+ *   round = round-half-to-even; scale and minimum are stored as fp16 and the quantizer uses the
+ *   stored (rounded) scale; a group is 32 consecutive tokens of one channel (Keys) or 32
+ *   consecutive channels of one token (Values); 3-bit blocks of 11 restart at every group
+ *   (11 + 11 + 10 = 32), so in-group elements 10 and 21 are the 2-bit ones and their step is
+ *   s*7/3 (the same range divided by q_max = 3); a zero-range group has scale 0 and codes 0.
+ *
+ * Pins (tests/test_oracle_*.py): brute-force nearest-level search, closed-form groups, the
+ * round-trip bound |x - x~| <= s_i/2, bijectivity of the packing, reduction to library
+ * attention when nothing is quantized, invariances of softmax attention.
+ * Parity unpinned: the physical bit order, the tie rule, the fp16 storage of scale/minimum and
+ * the 3-bit step reading are readings, the paper prints no worked numeric example.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define D_HEAD 128
+#define GROUP 32
+#define TILE_TOKENS 32
+
+enum { REF_OK = 0, REF_ERR_NULL = -1, REF_ERR_BAD_BITS = -2, REF_ERR_BAD_GROUP = -3, REF_ERR_BAD_SHAPE = -4 };
+
+typedef struct { int32_t B, Hq, Hkv, D, group; } ref_shape;
+typedef struct { int32_t k_bits, v_bits, window; } ref_layer_cfg;
+typedef struct {
+  uint32_t* k_codes; uint16_t* k_scale; uint16_t* k_zero;
+  uint32_t* v_codes; uint16_t* v_scale; uint16_t* v_zero;
+  uint16_t* k_win;   uint16_t* v_win;
+  int32_t T_cap, W_cap, n_q, n_w, w0;
+} ref_layer_cache; /* all pointers are host memory */
+
+/* ------------------------------------------------------------------ fp16 <-> binary64 */
+
+/* IEEE binary16 bit pattern -> value (exact). */
+double kvmix_ref_h2d(uint16_t h) {
+  int sign = h >> 15, e = (h >> 10) & 31, m = h & 1023;
+  double v;
+  if (e == 0) v = ldexp((double)m, -24);
+  else if (e == 31) v = m ? NAN : INFINITY;
+  else v = ldexp((double)(1024 + m), e - 25);
+  return sign ? -v : v;
+}
+
+/* value -> nearest binary16, ties to even, one rounding. */
+uint16_t kvmix_ref_d2h(double x) {
+  uint16_t sign = signbit(x) ? 0x8000u : 0;
+  double a = fabs(x);
+  if (isnan(a)) return sign | 0x7e00u;
+  if (isinf(a)) return sign | 0x7c00u;
+  if (a < ldexp(1.0, -14)) {               /* subnormal range: spacing 2^-24 */
+    long q = lrint(ldexp(a, 24));          /* lrint: current mode = nearest-even */
+    return sign | (uint16_t)q;             /* q == 1024 is the smallest normal, same bits */
+  }
+  int e;
+  double m = frexp(a, &e);                 /* a = m * 2^e, m in [0.5, 1) */
+  long q = lrint(ldexp(m, 11));            /* 11 significant bits: q in [1024, 2048] */
+  if (q == 2048) { q = 1024; e += 1; }
+  int E = e - 1 + 15;
+  if (E >= 31) return sign | 0x7c00u;      /* overflow -> inf */
+  return sign | (uint16_t)((E << 10) | (q - 1024));
+}
+
+static float h2f(uint16_t h) { return (float)kvmix_ref_h2d(h); }   /* exact */
+static uint16_t f2h(float f) { return kvmix_ref_d2h((double)f); }  /* one rounding */
+
+/* ------------------------------------------------------------------ quantizer (Sec. 3.2.2) */
+
+static int qmax_of(int bits) { return (1 << bits) - 1; }
+
+/* q_max of in-group element i: the case equation of Sec. 3.2.2 with blocks of 11 restarting
+ * at each group of 32, so block positions 10 fall on i = 10 and i = 21. */
+static int qmax_elem(int bits, int i) { return (bits == 3 && (i == 10 || i == 21)) ? 3 : qmax_of(bits); }
+
+/* step of in-group element i given the stored fp16 scale: the same range over its own q_max. */
+static float step_elem(int bits, int i, uint16_t scale_h) {
+  float s = h2f(scale_h);
+  if (qmax_elem(bits, i) == qmax_of(bits)) return s;
+  return (s * 7.0f) / 3.0f;
+}
+
+/* One group of 32 fp16 values -> 32 codes + fp16 scale + fp16 zero-point (the minimum). */
+void kvmix_ref_quantize_group(const uint16_t* x, int bits, uint8_t* code, uint16_t* scale_h, uint16_t* zero_h) {
+  float mn = h2f(x[0]), mx = h2f(x[0]);
+  for (int i = 1; i < GROUP; i++) {
+    float v = h2f(x[i]);
+    if (v < mn) mn = v;
+    if (v > mx) mx = v;
+  }
+  if (mn == 0.0f) mn = 0.0f * 0.0f;                 /* -0 -> +0 */
+  float range = mx - mn;                            /* step 1: s = (max - min) / q_max */
+  float s32 = range / (float)qmax_of(bits);
+  *scale_h = f2h(s32);
+  *zero_h = f2h(mn);                                /* exact: mn is an fp16 value */
+  float s = h2f(*scale_h);
+  for (int i = 0; i < GROUP; i++) {
+    if (s == 0.0f) { code[i] = 0; continue; }
+    float si = step_elem(bits, i, *scale_h);
+    float t = (h2f(x[i]) - mn) / si;                /* step 2: q = round((x - min) / s) */
+    float r = rintf(t);
+    float hi = (float)qmax_elem(bits, i);           /* step 3: clip to [0, q_max] */
+    if (r < 0.0f) r = 0.0f;
+    if (r > hi) r = hi;
+    code[i] = (uint8_t)r;
+  }
+}
+
+/* step 4: x = q * s + min, in exact (binary64) arithmetic on the stored quantities. */
+double kvmix_ref_dequant_elem(int code, int i, int bits, uint16_t scale_h, uint16_t zero_h) {
+  return (double)code * (double)step_elem(bits, i, scale_h) + kvmix_ref_h2d(zero_h);
+}
+
+/* ------------------------------------------------------------------ packed tile encoding */
+
+typedef struct { int word, bit, hword, hbit; } code_pos; /* hword < 0: no high plane */
+
+static int words_per_tile(int bits) { return 128 * bits; } /* 32 x 128 codes, 32 bits per word */
+
+/* Bit fields of one code given its lane column l, register j, half hh and slot numbers. */
+static code_pos pos_from_slots(int bits, int l, int j, int hh, int f2, int c4, int f4, int beta) {
+  code_pos p; p.hword = -1; p.hbit = 0;
+  if (bits == 4) { p.word = 256 * c4 + 4 * l + j; p.bit = 16 * hh + 4 * f4; return p; }
+  p.word = 4 * l + j; p.bit = 16 * hh + 2 * f2;
+  if (bits == 3) { p.hword = 256 + 2 * l + j / 2; p.hbit = 16 * hh + 8 * (j % 2) + beta; }
+  return p;
+}
+
+/* Key code of token tau (0..31) and channel d (0..127) inside its tile. */
+static code_pos pos_key(int bits, int tau, int d) {
+  int ks = d / 32, kq = (d % 32) / 8, j = (d % 8) / 2, hh = d % 2;
+  int m = (tau % 8) / 4, i = 4 * (tau / 8) + tau % 4;
+  return pos_from_slots(bits, 16 * kq + i, j, hh, ks + 4 * m, ks / 2, ks % 2 + 2 * m, 2 * ks + m);
+}
+
+/* Value code of token tau and channel d inside its tile. */
+static code_pos pos_value(int bits, int tau, int d) {
+  int kq = tau / 8, j = (tau % 8) / 2, hh = tau % 2;
+  int m = d / 16, i = d % 16;
+  return pos_from_slots(bits, 16 * kq + i, j, hh, m, m / 4, m % 4, 2 * (m % 4) + m / 4);
+}
+
+static void put_code(uint32_t* tile, int bits, code_pos p, int code) {
+  if (bits == 3) {
+    tile[p.word] |= (uint32_t)(code & 3) << p.bit;
+    tile[p.hword] |= (uint32_t)(code >> 2) << p.hbit;
+  } else {
+    tile[p.word] |= (uint32_t)code << p.bit;
+  }
+}
+
+static int get_code(const uint32_t* tile, int bits, code_pos p) {
+  if (bits == 3) return (int)((tile[p.word] >> p.bit) & 3u) + 4 * (int)((tile[p.hword] >> p.hbit) & 1u);
+  return (int)((tile[p.word] >> p.bit) & (uint32_t)qmax_of(bits));
+}
+
+/* codes[tau*128 + d] -> tile words (which = 0 Key, 1 Value); and back. */
+void kvmix_ref_pack_tile(int which, int bits, const uint8_t* codes, uint32_t* tile) {
+  memset(tile, 0, sizeof(uint32_t) * (size_t)words_per_tile(bits));
+  for (int tau = 0; tau < TILE_TOKENS; tau++)
+    for (int d = 0; d < D_HEAD; d++)
+      put_code(tile, bits, which ? pos_value(bits, tau, d) : pos_key(bits, tau, d), codes[tau * D_HEAD + d]);
+}
+
+void kvmix_ref_unpack_tile(int which, int bits, const uint32_t* tile, uint8_t* codes) {
+  for (int tau = 0; tau < TILE_TOKENS; tau++)
+    for (int d = 0; d < D_HEAD; d++)
+      codes[tau * D_HEAD + d] = (uint8_t)get_code(tile, bits, which ? pos_value(bits, tau, d) : pos_key(bits, tau, d));
+}
+
+/* ------------------------------------------------------------------ cache-level calls */
+
+static int check_common(const ref_shape* sh, const ref_layer_cfg* cfg) {
+  if (!sh || !cfg) return REF_ERR_NULL;
+  if (sh->group != GROUP) return REF_ERR_BAD_GROUP;
+  if (sh->D != D_HEAD || sh->B < 1 || sh->Hkv < 1 || sh->Hq < 1 || sh->Hq % sh->Hkv) return REF_ERR_BAD_SHAPE;
+  int kb = cfg->k_bits, vb = cfg->v_bits;
+  if (kb == 16 || vb == 16) return (kb == 16 && vb == 16) ? REF_OK : REF_ERR_BAD_BITS;
+  if (kb < 2 || kb > 4 || vb < 2 || vb > 4) return REF_ERR_BAD_BITS;
+  return REF_OK;
+}
+
+int kvmix_ref_num_threads(void) {
+#ifdef _OPENMP
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}
+
+/* Quantize-and-pack n_tokens tokens at token offset t0 of the packed cache.
+ * Element (b, j, t, d) of k/v is at b*batch_stride + j*head_stride + t*token_stride + d*chan_stride. */
+static int quantize_pack_strided(const ref_shape* sh, const ref_layer_cfg* cfg, const uint16_t* k, const uint16_t* v,
+                                 int64_t k_tok, int64_t k_chan, int64_t k_unit_b, int64_t k_unit_h,
+                                 int64_t v_tok, int64_t v_chan, int64_t v_unit_b, int64_t v_unit_h,
+                                 int n_tokens, int t0, const ref_layer_cache* c) {
+  int units = sh->B * sh->Hkv, tiles_cap = c->T_cap / TILE_TOKENS;
+  int kb = cfg->k_bits, vb = cfg->v_bits;
+#pragma omp parallel for schedule(static)
+  for (int u = 0; u < units; u++) {
+    int b = u / sh->Hkv, j = u % sh->Hkv;
+    const uint16_t* ku = k + b * k_unit_b + j * k_unit_h;
+    const uint16_t* vu = v + b * v_unit_b + j * v_unit_h;
+    for (int tt = 0; tt < n_tokens / TILE_TOKENS; tt++) {
+      size_t tile = (size_t)u * tiles_cap + (size_t)(t0 / TILE_TOKENS + tt);
+      uint8_t codes[TILE_TOKENS * D_HEAD];
+      uint16_t x[GROUP]; uint8_t gc[GROUP];
+      /* Keys: one group per channel, along the 32 tokens of the tile (Sec. 3.2.1) */
+      for (int d = 0; d < D_HEAD; d++) {
+        for (int tau = 0; tau < TILE_TOKENS; tau++) x[tau] = ku[(int64_t)(tt * TILE_TOKENS + tau) * k_tok + d * k_chan];
+        kvmix_ref_quantize_group(x, kb, gc, &c->k_scale[tile * D_HEAD + d], &c->k_zero[tile * D_HEAD + d]);
+        for (int tau = 0; tau < TILE_TOKENS; tau++) codes[tau * D_HEAD + d] = gc[tau];
+      }
+      kvmix_ref_pack_tile(0, kb, codes, c->k_codes + tile * words_per_tile(kb));
+      /* Values: one group per (token, 32-channel block) */
+      for (int tau = 0; tau < TILE_TOKENS; tau++)
+        for (int g = 0; g < D_HEAD / GROUP; g++) {
+          for (int e = 0; e < GROUP; e++) x[e] = vu[(int64_t)(tt * TILE_TOKENS + tau) * v_tok + (g * GROUP + e) * v_chan];
+          size_t mi = tile * D_HEAD + (size_t)g * TILE_TOKENS + tau;   /* [tile][g][tau] */
+          kvmix_ref_quantize_group(x, vb, gc, &c->v_scale[mi], &c->v_zero[mi]);
+          for (int e = 0; e < GROUP; e++) codes[tau * D_HEAD + g * GROUP + e] = gc[e];
+        }
+      kvmix_ref_pack_tile(1, vb, codes, c->v_codes + tile * words_per_tile(vb));
+    }
+  }
+  return REF_OK;
+}
+
+int kvmix_ref_quantize_pack(const ref_shape* sh, const ref_layer_cfg* cfg, const uint16_t* k, const uint16_t* v,
+                            int64_t token_stride, int64_t head_stride, int64_t batch_stride,
+                            int n_tokens, int t0, const ref_layer_cache* c) {
+  int st = check_common(sh, cfg);
+  if (st) return st;
+  if (!k || !v || !c) return REF_ERR_NULL;
+  if (cfg->k_bits == 16) return REF_ERR_BAD_BITS;
+  if (n_tokens < 0 || n_tokens % TILE_TOKENS || t0 < 0 || t0 % TILE_TOKENS || t0 + n_tokens > c->T_cap) return REF_ERR_BAD_SHAPE;
+  return quantize_pack_strided(sh, cfg, k, v, token_stride, 1, batch_stride, head_stride,
+                               token_stride, 1, batch_stride, head_stride, n_tokens, t0, c);
+}
+
+/* Append one token per unit to the window ring; flush the oldest 32 into the packed cache when
+ * the window holds window + 32 tokens (Sec. 3.3: older tokens are quantized, recent ones stay). */
+int kvmix_ref_append(const ref_shape* sh, const ref_layer_cfg* cfg, const uint16_t* k_new, const uint16_t* v_new,
+                     ref_layer_cache* c) {
+  int st = check_common(sh, cfg);
+  if (st) return st;
+  if (!k_new || !v_new || !c) return REF_ERR_NULL;
+  if (c->n_w >= c->W_cap) return REF_ERR_BAD_SHAPE;
+  int units = sh->B * sh->Hkv, W = c->W_cap;
+  int slot = (c->w0 + c->n_w) % W;
+  for (int u = 0; u < units; u++)
+    for (int d = 0; d < D_HEAD; d++) {
+      c->k_win[((size_t)u * W + slot) * D_HEAD + d] = k_new[(size_t)u * D_HEAD + d];
+      c->v_win[((size_t)u * D_HEAD + d) * W + slot] = v_new[(size_t)u * D_HEAD + d];
+    }
+  c->n_w += 1;
+  if (cfg->k_bits != 16 && c->n_w == cfg->window + TILE_TOKENS) {
+    if (c->n_q + TILE_TOKENS > c->T_cap) return REF_ERR_BAD_SHAPE;
+    /* the oldest 32 tokens are slots w0 .. w0+31 (w0 and W_cap are multiples of 32) */
+    st = quantize_pack_strided(sh, cfg, c->k_win + (size_t)c->w0 * D_HEAD, c->v_win + c->w0,
+                               D_HEAD, 1, (int64_t)sh->Hkv * W * D_HEAD, (int64_t)W * D_HEAD,
+                               1, W, (int64_t)sh->Hkv * D_HEAD * W, (int64_t)D_HEAD * W,
+                               TILE_TOKENS, c->n_q, c);
+    if (st) return st;
+    c->n_q += TILE_TOKENS;
+    c->n_w -= TILE_TOKENS;
+    c->w0 = (c->w0 + TILE_TOKENS) % W;
+  }
+  return REF_OK;
+}
+
+/* Dequantized packed tokens of one unit as binary64: out[t*128 + d], t < n_q. */
+static void dequant_unit(const ref_shape* sh, int bits, int which, const ref_layer_cache* c, int u, double* out) {
+  (void)sh;
+  int tiles_cap = c->T_cap / TILE_TOKENS;
+  const uint32_t* codes_base = which ? c->v_codes : c->k_codes;
+  const uint16_t* sc = which ? c->v_scale : c->k_scale;
+  const uint16_t* zr = which ? c->v_zero : c->k_zero;
+  uint8_t codes[TILE_TOKENS * D_HEAD];
+  for (int tt = 0; tt < c->n_q / TILE_TOKENS; tt++) {
+    size_t tile = (size_t)u * tiles_cap + tt;
+    kvmix_ref_unpack_tile(which, bits, codes_base + tile * words_per_tile(bits), codes);
+    for (int tau = 0; tau < TILE_TOKENS; tau++)
+      for (int d = 0; d < D_HEAD; d++) {
+        size_t mi; int i;
+        if (which == 0) { mi = tile * D_HEAD + d; i = tau; }                       /* group along tokens */
+        else { mi = tile * D_HEAD + (size_t)(d / GROUP) * TILE_TOKENS + tau; i = d % GROUP; } /* along channels */
+        out[(size_t)(tt * TILE_TOKENS + tau) * D_HEAD + d] = kvmix_ref_dequant_elem(codes[tau * D_HEAD + d], i, bits, sc[mi], zr[mi]);
+      }
+  }
+}
+
+int kvmix_ref_dequant(const ref_shape* sh, const ref_layer_cfg* cfg, const ref_layer_cache* c, int which, double* out) {
+  int st = check_common(sh, cfg);
+  if (st) return st;
+  if (!c || !out) return REF_ERR_NULL;
+  if (cfg->k_bits == 16) return c->n_q == 0 ? REF_OK : REF_ERR_BAD_BITS;
+  int units = sh->B * sh->Hkv;
+  for (int u = 0; u < units; u++)
+    dequant_unit(sh, which ? cfg->v_bits : cfg->k_bits, which, c, u, out + (size_t)u * c->n_q * D_HEAD);
+  return REF_OK;
+}
+
+/* Decode attention by definition. q, out: fp16 [B][Hq][128]. */
+int kvmix_ref_decode_attn(const ref_shape* sh, const ref_layer_cfg* cfg, const uint16_t* q, const ref_layer_cache* c,
+                          float softmax_scale, uint16_t* out) {
+  int st = check_common(sh, cfg);
+  if (st) return st;
+  if (!q || !c || !out) return REF_ERR_NULL;
+  if (cfg->k_bits == 16 && c->n_q != 0) return REF_ERR_BAD_BITS;
+  if (c->n_q + c->n_w < 1 || c->n_q % TILE_TOKENS || c->n_w > c->W_cap) return REF_ERR_BAD_SHAPE;
+  int units = sh->B * sh->Hkv, G = sh->Hq / sh->Hkv, T = c->n_q + c->n_w, W = c->W_cap;
+  double scale = softmax_scale > 0.0f ? (double)softmax_scale : 1.0 / sqrt((double)D_HEAD);
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int u = 0; u < units; u++) {
+    int b = u / sh->Hkv, j = u % sh->Hkv;
+    double* Kt = (double*)malloc(sizeof(double) * (size_t)T * D_HEAD);
+    double* Vt = (double*)malloc(sizeof(double) * (size_t)T * D_HEAD);
+    double* a = (double*)malloc(sizeof(double) * (size_t)T);
+    if (c->n_q) { dequant_unit(sh, cfg->k_bits, 0, c, u, Kt); dequant_unit(sh, cfg->v_bits, 1, c, u, Vt); }
+    for (int r = 0; r < c->n_w; r++) {                   /* window tokens, oldest first */
+      int slot = (c->w0 + r) % W;
+      for (int d = 0; d < D_HEAD; d++) {
+        Kt[(size_t)(c->n_q + r) * D_HEAD + d] = kvmix_ref_h2d(c->k_win[((size_t)u * W + slot) * D_HEAD + d]);
+        Vt[(size_t)(c->n_q + r) * D_HEAD + d] = kvmix_ref_h2d(c->v_win[((size_t)u * D_HEAD + d) * W + slot]);
+      }
+    }
+    for (int hg = 0; hg < G; hg++) {
+      int h = j * G + hg;                                /* query head h reads kv head h / G */
+      const uint16_t* qh = q + ((size_t)b * sh->Hq + h) * D_HEAD;
+      double m = -INFINITY;
+      for (int t = 0; t < T; t++) {
+        double acc = 0.0;
+        for (int d = 0; d < D_HEAD; d++) acc += kvmix_ref_h2d(qh[d]) * Kt[(size_t)t * D_HEAD + d];
+        a[t] = scale * acc;
+        if (a[t] > m) m = a[t];
+      }
+      double l = 0.0;
+      for (int t = 0; t < T; t++) { a[t] = exp(a[t] - m); l += a[t]; }
+      for (int d = 0; d < D_HEAD; d++) {
+        double o = 0.0;
+        for (int t = 0; t < T; t++) o += a[t] * Vt[(size_t)t * D_HEAD + d];
+        out[((size_t)b * sh->Hq + h) * D_HEAD + d] = kvmix_ref_d2h(o / l);
+      }
+    }
+    free(Kt); free(Vt); free(a);
+  }
+  return REF_OK;
+}
