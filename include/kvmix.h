@@ -38,14 +38,13 @@
  *   inside its tile is given below. "lane" l = 0..63 names the 16-byte column of a 1 KiB
  *   block, l = 16*kq + i.
  *     Key code (tau, d):   ks = d/32, kq = (d%32)/8, j = (d%8)/2, hh = d%2,
- *                          m = (tau%8)/4, i = 4*(tau/8) + tau%4
- *     Value code (tau, d): kq = tau/8, j = (tau%8)/2, hh = tau%2, m = d/16 (0..7), i = d%16
- *     2-bit: word 4*l + j, bits [16*hh + 2*f, +2), f = ks + 4*m (Key) or f = m (Value).
- *     4-bit: word 256*c + 4*l + j, bits [16*hh + 4*f, +4),
- *            Key: c = ks/2, f = ks%2 + 2*m;  Value: c = m/4, f = m%4.
+ *                          m = (tau%8)/4, i = 4*(tau/8) + tau%4, slot = ks + 4*m
+ *     Value code (tau, d): kq = tau/8, j = (tau%8)/2, hh = tau%2, i = d%16, slot = d/16
+ *     2-bit: word 4*l + j, bits [16*hh + 2*slot, +2).
+ *     4-bit: word 256*(slot/4) + 4*l + j, bits [16*hh + 4*(slot%4), +4).
  *     3-bit: code = lo + 4*hi. The 2-bit plane `lo` is stored exactly like a 2-bit tile
  *            (256 words), followed by the 1-bit plane `hi` (128 words): word 256 + 2*l + j/2,
- *            bit 16*hh + 8*(j%2) + beta, beta = 2*ks + m (Key) or 2*(m%4) + m/4 (Value).
+ *            bit 16*hh + 8*(j%2) + 2*(slot%4) + slot/4.
  *            The two elements of every group that the paper stores with 2 bits (in-group
  *            index 10 and 21: the 11th element of the first and second block of 11) have
  *            hi = 0 by construction, so a group occupies 3 words = 30*3 + 2*2 + 2 unused bits,

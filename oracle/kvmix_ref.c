@@ -137,27 +137,34 @@ typedef struct { int word, bit, hword, hbit; } code_pos; /* hword < 0: no high p
 
 static int words_per_tile(int bits) { return 128 * bits; } /* 32 x 128 codes, 32 bits per word */
 
-/* Bit fields of one code given its lane column l, register j, half hh and slot numbers. */
-static code_pos pos_from_slots(int bits, int l, int j, int hh, int f2, int c4, int f4, int beta) {
+/* Bit fields of one code given the 16-byte column l (0..63) of its 1 KiB block, the word j
+ * (0..3) inside the column, the 16-bit half hh of the word and its slot (0..7) inside the half.
+ *   2 bit: word 4l + j, bits [16hh + 2 slot, +2)
+ *   4 bit: word 256 (slot/4) + 4l + j, bits [16hh + 4 (slot%4), +4)
+ *   3 bit: code = lo + 4 hi; lo stored like a 2-bit tile, hi in a 1-bit plane after it:
+ *          word 256 + 2l + j/2, bit 16hh + 8 (j%2) + 2 (slot%4) + slot/4 */
+static code_pos pos_from_slots(int bits, int l, int j, int hh, int slot) {
   code_pos p; p.hword = -1; p.hbit = 0;
-  if (bits == 4) { p.word = 256 * c4 + 4 * l + j; p.bit = 16 * hh + 4 * f4; return p; }
-  p.word = 4 * l + j; p.bit = 16 * hh + 2 * f2;
-  if (bits == 3) { p.hword = 256 + 2 * l + j / 2; p.hbit = 16 * hh + 8 * (j % 2) + beta; }
+  if (bits == 4) { p.word = 256 * (slot / 4) + 4 * l + j; p.bit = 16 * hh + 4 * (slot % 4); return p; }
+  p.word = 4 * l + j; p.bit = 16 * hh + 2 * slot;
+  if (bits == 3) { p.hword = 256 + 2 * l + j / 2; p.hbit = 16 * hh + 8 * (j % 2) + 2 * (slot % 4) + slot / 4; }
   return p;
 }
 
-/* Key code of token tau (0..31) and channel d (0..127) inside its tile. */
+/* Key code of token tau (0..31) and channel d (0..127) inside its tile: a word pairs two
+ * adjacent channels in its halves, its slots run over channel blocks of 32 and token halves. */
 static code_pos pos_key(int bits, int tau, int d) {
   int ks = d / 32, kq = (d % 32) / 8, j = (d % 8) / 2, hh = d % 2;
   int m = (tau % 8) / 4, i = 4 * (tau / 8) + tau % 4;
-  return pos_from_slots(bits, 16 * kq + i, j, hh, ks + 4 * m, ks / 2, ks % 2 + 2 * m, 2 * ks + m);
+  return pos_from_slots(bits, 16 * kq + i, j, hh, ks + 4 * m);
 }
 
-/* Value code of token tau and channel d inside its tile. */
+/* Value code of token tau and channel d inside its tile: a word pairs two adjacent tokens in
+ * its halves, its slots run over channel blocks of 16. */
 static code_pos pos_value(int bits, int tau, int d) {
   int kq = tau / 8, j = (tau % 8) / 2, hh = tau % 2;
   int m = d / 16, i = d % 16;
-  return pos_from_slots(bits, 16 * kq + i, j, hh, m, m / 4, m % 4, 2 * (m % 4) + m / 4);
+  return pos_from_slots(bits, 16 * kq + i, j, hh, m);
 }
 
 static void put_code(uint32_t* tile, int bits, code_pos p, int code) {

@@ -155,9 +155,9 @@ class RefCache:
 
     def set_window(self, k, v):
         """k, v: uint16 [B][Hkv][n_w][128]: the window tokens, oldest first (ring start reset to 0)."""
-        k = np.asarray(k, dtype=np.uint16).reshape(self.units, -1, 128)
-        v = np.asarray(v, dtype=np.uint16).reshape(self.units, -1, 128)
-        n = k.shape[1]
+        n = k.shape[2]
+        k = np.asarray(k, dtype=np.uint16).reshape(self.units, n, 128)
+        v = np.asarray(v, dtype=np.uint16).reshape(self.units, n, 128)
         assert n <= self.c.W_cap
         self.k_win[:, :n, :] = k
         self.v_win[:, :, :n] = v.transpose(0, 2, 1)

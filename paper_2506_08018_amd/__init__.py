@@ -1,0 +1,10 @@
+"""KVmix hot path on MI355X: thin Python binding over the C-ABI library libkvmix.so.
+
+Every step of the path runs in the HIP kernels of csrc/; this package only marshals arguments.
+PyTorch is used for device memory and streams.
+"""
+from .binding import (KVMixError, LayerCache, LayerCfg, Shape, append, cache_bytes, decode_attn, dequant, lib,
+                      quantize_pack, strerror, version, workspace_bytes)
+
+__all__ = ["KVMixError", "LayerCache", "LayerCfg", "Shape", "append", "cache_bytes", "decode_attn", "dequant", "lib",
+           "quantize_pack", "strerror", "version", "workspace_bytes"]

@@ -1,0 +1,169 @@
+"""ctypes marshalling for include/kvmix.h. No arithmetic of the method lives here."""
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libkvmix.so")
+_lib = None
+
+
+class KVMixError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__(f"{where}: {strerror(status)} (status {status})")
+
+
+class Shape(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("B", "Hq", "Hkv", "D", "group")]
+
+    def __init__(self, B, Hq, Hkv, D=128, group=32):
+        super().__init__(B, Hq, Hkv, D, group)
+
+    @property
+    def units(self):
+        return self.B * self.Hkv
+
+
+class LayerCfg(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("k_bits", "v_bits", "window")]
+
+
+class _CacheStruct(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("k_codes", "k_scale", "k_zero", "v_codes", "v_scale", "v_zero", "k_win", "v_win")] + \
+               [(n, C.c_int32) for n in ("T_cap", "W_cap", "n_q", "n_w", "w0")]
+
+
+def lib():
+    """Load libkvmix.so (built in-tree by paper_2506_08018_amd/build.py). Fails loudly when it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_2506_08018_amd.build` "
+                              "(there is no CPU fallback)")
+        L = C.CDLL(_LIB_PATH)
+        P, I, I64, SZ = C.c_void_p, C.c_int, C.c_int64, C.c_size_t
+        L.kvmix_version.restype = I
+        L.kvmix_strerror.restype = C.c_char_p
+        L.kvmix_strerror.argtypes = [I]
+        L.kvmix_last_hip_error.restype = I
+        L.kvmix_cache_bytes.restype = I
+        L.kvmix_cache_bytes.argtypes = [P, P, I, I] + [P] * 5
+        L.kvmix_workspace_bytes.restype = I
+        L.kvmix_workspace_bytes.argtypes = [P, I, P]
+        L.kvmix_quantize_pack.restype = I
+        L.kvmix_quantize_pack.argtypes = [P, P, P, P, I64, I64, I64, I, I, P, P]
+        L.kvmix_append.restype = I
+        L.kvmix_append.argtypes = [P, P, P, P, P, P]
+        L.kvmix_decode_attn.restype = I
+        L.kvmix_decode_attn.argtypes = [P, P, P, P, C.c_float, P, P, SZ, I, P]
+        L.kvmix_dequant.restype = I
+        L.kvmix_dequant.argtypes = [P, P, P, I, P, P]
+        _lib = L
+    return _lib
+
+
+def version():
+    return lib().kvmix_version()
+
+
+def strerror(status):
+    return lib().kvmix_strerror(int(status)).decode()
+
+
+def _check(status, where):
+    if status != 0:
+        raise KVMixError(status, where)
+
+
+def _stream():
+    import torch
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def cache_bytes(shape, cfg, T_cap, W_cap):
+    """-> dict of byte sizes (k_code, k_meta, v_code, v_meta, win)."""
+    out = [C.c_size_t(0) for _ in range(5)]
+    _check(lib().kvmix_cache_bytes(C.byref(shape), C.byref(cfg), T_cap, W_cap, *[C.byref(o) for o in out]), "kvmix_cache_bytes")
+    return dict(zip(("k_code", "k_meta", "v_code", "v_meta", "win"), (o.value for o in out)))
+
+
+def workspace_bytes(shape, T_max):
+    n = C.c_size_t(0)
+    _check(lib().kvmix_workspace_bytes(C.byref(shape), T_max, C.byref(n)), "kvmix_workspace_bytes")
+    return n.value
+
+
+class LayerCache:
+    """One layer's cache: device buffers (torch uint8/int16 tensors) plus the host-side struct."""
+
+    def __init__(self, shape, cfg, T_cap, W_cap, device="cuda"):
+        import torch
+        self.shape, self.cfg = shape, cfg
+        sz = cache_bytes(shape, cfg, T_cap, W_cap)
+        z = lambda n: torch.zeros(max(n, 16), dtype=torch.uint8, device=device)
+        self.k_codes, self.v_codes = z(sz["k_code"]), z(sz["v_code"])
+        self.k_scale, self.k_zero = z(sz["k_meta"]), z(sz["k_meta"])
+        self.v_scale, self.v_zero = z(sz["v_meta"]), z(sz["v_meta"])
+        self.k_win, self.v_win = z(sz["win"]), z(sz["win"])
+        self.c = _CacheStruct(self.k_codes.data_ptr(), self.k_scale.data_ptr(), self.k_zero.data_ptr(),
+                              self.v_codes.data_ptr(), self.v_scale.data_ptr(), self.v_zero.data_ptr(),
+                              self.k_win.data_ptr(), self.v_win.data_ptr(), T_cap, W_cap, 0, 0, 0)
+
+    n_q = property(lambda self: self.c.n_q)
+    n_w = property(lambda self: self.c.n_w)
+    w0 = property(lambda self: self.c.w0)
+    T_cap = property(lambda self: self.c.T_cap)
+    W_cap = property(lambda self: self.c.W_cap)
+
+    def nbytes(self):
+        return sum(t.numel() for t in (self.k_codes, self.v_codes, self.k_scale, self.k_zero, self.v_scale, self.v_zero,
+                                       self.k_win, self.v_win))
+
+    def set_window(self, k, v):
+        """k, v: fp16 tensors [B][Hkv][n_w][128] (oldest first); plain copies into the ring, start slot 0."""
+        import torch
+        units, W = self.shape.units, self.c.W_cap
+        n = k.shape[2]
+        assert n <= W
+        kw = self.k_win.view(torch.float16).view(units, W, 128)
+        vw = self.v_win.view(torch.float16).view(units, 128, W)
+        kw[:, :n, :] = k.reshape(units, n, 128)
+        vw[:, :, :n] = v.reshape(units, n, 128).transpose(1, 2)
+        self.c.n_w = n
+        self.c.w0 = 0
+
+
+def quantize_pack(shape, cfg, k, v, cache, t0=None):
+    """k, v: fp16 CUDA tensors [B][Hkv][n_tokens][128] (last dim contiguous). Writes at token offset t0
+    (default n_q) and advances cache.n_q."""
+    assert k.dtype == v.dtype and k.element_size() == 2 and k.stride(3) == 1 and v.stride() == k.stride()
+    n = k.shape[2]
+    if t0 is None:
+        t0 = cache.c.n_q
+    st = lib().kvmix_quantize_pack(C.byref(shape), C.byref(cfg), k.data_ptr(), v.data_ptr(), k.stride(2), k.stride(1),
+                                   k.stride(0), n, t0, C.byref(cache.c), _stream())
+    _check(st, "kvmix_quantize_pack")
+    cache.c.n_q = max(cache.c.n_q, t0 + n)
+
+
+def append(shape, cfg, k_new, v_new, cache):
+    """k_new, v_new: fp16 CUDA tensors [B][Hkv][128], contiguous."""
+    assert k_new.is_contiguous() and v_new.is_contiguous()
+    _check(lib().kvmix_append(C.byref(shape), C.byref(cfg), k_new.data_ptr(), v_new.data_ptr(), C.byref(cache.c), _stream()),
+           "kvmix_append")
+
+
+def decode_attn(shape, cfg, q, cache, out, workspace=None, softmax_scale=0.0, n_splits=0):
+    """q, out: fp16 CUDA tensors [B][Hq][128], contiguous. workspace: uint8 CUDA tensor (zeroed once) or None."""
+    assert q.is_contiguous() and out.is_contiguous()
+    wp, wn = (workspace.data_ptr(), workspace.numel() * workspace.element_size()) if workspace is not None else (None, 0)
+    st = lib().kvmix_decode_attn(C.byref(shape), C.byref(cfg), q.data_ptr(), C.byref(cache.c), C.c_float(softmax_scale),
+                                 out.data_ptr(), wp, wn, n_splits, _stream())
+    _check(st, "kvmix_decode_attn")
+    return out
+
+
+def dequant(shape, cfg, cache, which, out):
+    """out: fp32 CUDA tensor [units][n_q][128]."""
+    _check(lib().kvmix_dequant(C.byref(shape), C.byref(cfg), C.byref(cache.c), which, out.data_ptr(), _stream()), "kvmix_dequant")
+    return out

@@ -1,0 +1,238 @@
+// C-ABI entry points of libkvmix: host-side validation and launch plumbing only.
+// Contract and layout: include/kvmix.h.
+#include <atomic>
+#include <cmath>
+#include "kvmix_common.hpp"
+
+using namespace kvmix;
+
+namespace {
+
+std::atomic<int> g_last_hip_error{0};
+
+int hip_fail(hipError_t e) {
+  g_last_hip_error.store((int)e);
+  return KVMIX_ERR_HIP;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_shape_cfg(const kvmix_shape* sh, const kvmix_layer_cfg* cfg) {
+  if (!sh || !cfg) return KVMIX_ERR_NULL;
+  if (sh->group != kTile) return KVMIX_ERR_BAD_GROUP;
+  if (sh->D != kD || sh->B < 1 || sh->Hkv < 1 || sh->Hq < 1 || sh->Hq % sh->Hkv) return KVMIX_ERR_BAD_SHAPE;
+  const int G = sh->Hq / sh->Hkv;
+  if (G != 1 && G != 2 && G != 4 && G != 8) return KVMIX_ERR_BAD_SHAPE;
+  if ((long long)sh->B * sh->Hkv > 65535) return KVMIX_ERR_BAD_SHAPE;
+  const int kb = cfg->k_bits, vb = cfg->v_bits;
+  if (kb == 16 || vb == 16) {
+    if (kb != 16 || vb != 16) return KVMIX_ERR_BAD_BITS;
+  } else if (kb < 2 || kb > 4 || vb < 2 || vb > 4) {
+    return KVMIX_ERR_BAD_BITS;
+  }
+  if (cfg->window < 0 || cfg->window % kTile) return KVMIX_ERR_BAD_SHAPE;
+  return KVMIX_OK;
+}
+
+int check_cache(const kvmix_layer_cfg* cfg, const kvmix_layer_cache* c, bool need_packed) {
+  if (!c) return KVMIX_ERR_NULL;
+  if (c->T_cap < 0 || c->T_cap % kTile || c->W_cap < kTile || c->W_cap % kTile) return KVMIX_ERR_BAD_SHAPE;
+  if (c->n_q < 0 || c->n_q % kTile || c->n_q > c->T_cap) return KVMIX_ERR_BAD_SHAPE;
+  if (c->n_w < 0 || c->n_w > c->W_cap || c->w0 < 0 || c->w0 >= c->W_cap || c->w0 % kTile) return KVMIX_ERR_BAD_SHAPE;
+  if (!c->k_win || !c->v_win) return KVMIX_ERR_NULL;
+  if (!aligned16(c->k_win) || !aligned16(c->v_win)) return KVMIX_ERR_ALIGN;
+  if (cfg->k_bits == 16) return c->n_q == 0 ? KVMIX_OK : KVMIX_ERR_BAD_BITS;
+  if (need_packed || c->n_q > 0) {
+    if (!c->k_codes || !c->k_scale || !c->k_zero || !c->v_codes || !c->v_scale || !c->v_zero) return KVMIX_ERR_NULL;
+    if (!aligned16(c->k_codes) || !aligned16(c->k_scale) || !aligned16(c->k_zero) || !aligned16(c->v_codes) ||
+        !aligned16(c->v_scale) || !aligned16(c->v_zero))
+      return KVMIX_ERR_ALIGN;
+  }
+  return KVMIX_OK;
+}
+
+int max_splits(const kvmix_shape* sh) {
+  const int units = sh->B * sh->Hkv;
+  int s = 512 / units;
+  if (s < 8) s = 8;
+  if (s > 64) s = 64;
+  return s;
+}
+
+size_t counters_bytes(int units) { return (((size_t)units * 4 + 255) / 256) * 256; }
+
+void fill_quant_dst(QuantArgs& a, const kvmix_layer_cache* c) {
+  a.k_codes = c->k_codes; a.k_scale = c->k_scale; a.k_zero = c->k_zero;
+  a.v_codes = c->v_codes; a.v_scale = c->v_scale; a.v_zero = c->v_zero;
+  a.tiles_cap = c->T_cap / kTile;
+}
+
+}  // namespace
+
+extern "C" {
+
+int kvmix_version(void) { return 1; }
+
+const char* kvmix_strerror(int status) {
+  switch (status) {
+    case KVMIX_OK: return "ok";
+    case KVMIX_ERR_NULL: return "null pointer";
+    case KVMIX_ERR_BAD_BITS: return "unsupported bit-width";
+    case KVMIX_ERR_BAD_GROUP: return "unsupported group size";
+    case KVMIX_ERR_BAD_SHAPE: return "unsupported shape or count";
+    case KVMIX_ERR_ALIGN: return "misaligned pointer or stride";
+    case KVMIX_ERR_WORKSPACE: return "workspace too small";
+    case KVMIX_ERR_HIP: return "HIP error";
+  }
+  return "unknown status";
+}
+
+int kvmix_last_hip_error(void) { return g_last_hip_error.load(); }
+
+int kvmix_cache_bytes(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, int T_cap, int W_cap,
+                      size_t* k_code_b, size_t* k_meta_b, size_t* v_code_b, size_t* v_meta_b, size_t* win_b) {
+  const int st = check_shape_cfg(sh, cfg);
+  if (st) return st;
+  if (T_cap < 0 || T_cap % kTile || W_cap < kTile || W_cap % kTile) return KVMIX_ERR_BAD_SHAPE;
+  const size_t units = (size_t)sh->B * sh->Hkv, tiles = (size_t)T_cap / kTile;
+  const bool packed = cfg->k_bits != 16;
+  if (k_code_b) *k_code_b = packed ? units * tiles * tile_words(cfg->k_bits) * 4 : 0;
+  if (v_code_b) *v_code_b = packed ? units * tiles * tile_words(cfg->v_bits) * 4 : 0;
+  if (k_meta_b) *k_meta_b = packed ? units * tiles * kD * 2 : 0;
+  if (v_meta_b) *v_meta_b = packed ? units * tiles * kD * 2 : 0;
+  if (win_b) *win_b = units * (size_t)W_cap * kD * 2;
+  return KVMIX_OK;
+}
+
+int kvmix_workspace_bytes(const kvmix_shape* sh, int T_max, size_t* bytes) {
+  kvmix_layer_cfg cfg = {2, 2, 0};
+  const int st = check_shape_cfg(sh, &cfg);
+  if (st) return st;
+  if (!bytes) return KVMIX_ERR_NULL;
+  if (T_max < 0) return KVMIX_ERR_BAD_SHAPE;
+  const size_t units = (size_t)sh->B * sh->Hkv, G = (size_t)(sh->Hq / sh->Hkv);
+  *bytes = counters_bytes((int)units) + units * (size_t)max_splits(sh) * G * (kD + 2) * sizeof(float);
+  return KVMIX_OK;
+}
+
+int kvmix_quantize_pack(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const uint16_t* k_fp16, const uint16_t* v_fp16,
+                        int64_t token_stride, int64_t head_stride, int64_t batch_stride, int n_tokens, int t0,
+                        const kvmix_layer_cache* c, void* stream) {
+  int st = check_shape_cfg(sh, cfg);
+  if (st) return st;
+  if (cfg->k_bits == 16) return KVMIX_ERR_BAD_BITS;
+  if (!k_fp16 || !v_fp16) return KVMIX_ERR_NULL;
+  st = check_cache(cfg, c, true);
+  if (st) return st;
+  if (n_tokens < 0 || n_tokens % kTile || t0 < 0 || t0 % kTile || (long long)t0 + n_tokens > c->T_cap) return KVMIX_ERR_BAD_SHAPE;
+  if (!aligned16(k_fp16) || !aligned16(v_fp16) || token_stride % 8 || head_stride % 8 || batch_stride % 8 || token_stride < kD)
+    return KVMIX_ERR_ALIGN;
+  QuantArgs a{};
+  a.k = k_fp16; a.v = v_fp16;
+  a.k_tok = token_stride; a.k_unit_b = batch_stride; a.k_unit_h = head_stride;
+  a.v_tok = token_stride; a.v_chan = 1; a.v_unit_b = batch_stride; a.v_unit_h = head_stride;
+  fill_quant_dst(a, c);
+  a.tile0 = t0 / kTile;
+  a.Hkv = sh->Hkv;
+  const hipError_t e = launch_quantize_pack(a, cfg->k_bits, cfg->v_bits, false, n_tokens / kTile, sh->B * sh->Hkv, (hipStream_t)stream);
+  return e == hipSuccess ? KVMIX_OK : hip_fail(e);
+}
+
+int kvmix_append(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const uint16_t* k_new, const uint16_t* v_new,
+                 kvmix_layer_cache* c, void* stream) {
+  int st = check_shape_cfg(sh, cfg);
+  if (st) return st;
+  if (!k_new || !v_new) return KVMIX_ERR_NULL;
+  st = check_cache(cfg, c, cfg->k_bits != 16);
+  if (st) return st;
+  if (c->n_w >= c->W_cap) return KVMIX_ERR_BAD_SHAPE;
+  const bool flush = cfg->k_bits != 16 && c->n_w + 1 == cfg->window + kTile;
+  if (cfg->k_bits != 16 && c->W_cap < cfg->window + kTile) return KVMIX_ERR_BAD_SHAPE;
+  if (flush && c->n_q + kTile > c->T_cap) return KVMIX_ERR_BAD_SHAPE;
+  const int units = sh->B * sh->Hkv, W = c->W_cap;
+  AppendArgs ap{};
+  ap.k_new = k_new; ap.v_new = v_new; ap.k_win = c->k_win; ap.v_win = c->v_win;
+  ap.W_cap = W; ap.slot = (c->w0 + c->n_w) % W; ap.units = units;
+  hipError_t e = launch_append(ap, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e);
+  c->n_w += 1;
+  if (flush) {
+    // the oldest 32 tokens are ring slots w0 .. w0+31; same quantizer, destination tile n_q/32
+    QuantArgs a{};
+    a.k = c->k_win + (size_t)c->w0 * kD;
+    a.v = c->v_win + c->w0;
+    a.k_tok = kD; a.k_unit_b = (int64_t)sh->Hkv * W * kD; a.k_unit_h = (int64_t)W * kD;
+    a.v_tok = 1; a.v_chan = W; a.v_unit_b = (int64_t)sh->Hkv * kD * W; a.v_unit_h = (int64_t)kD * W;
+    fill_quant_dst(a, c);
+    a.tile0 = c->n_q / kTile;
+    a.Hkv = sh->Hkv;
+    e = launch_quantize_pack(a, cfg->k_bits, cfg->v_bits, true, 1, units, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(e);
+    c->n_q += kTile;
+    c->n_w -= kTile;
+    c->w0 = (c->w0 + kTile) % W;
+  }
+  return KVMIX_OK;
+}
+
+int kvmix_decode_attn(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const uint16_t* q, const kvmix_layer_cache* c,
+                      float softmax_scale, uint16_t* out, void* workspace, size_t workspace_bytes, int n_splits, void* stream) {
+  int st = check_shape_cfg(sh, cfg);
+  if (st) return st;
+  if (!q || !out) return KVMIX_ERR_NULL;
+  if (!aligned16(q) || !aligned16(out)) return KVMIX_ERR_ALIGN;
+  st = check_cache(cfg, c, false);
+  if (st) return st;
+  if (c->n_q + c->n_w < 1) return KVMIX_ERR_BAD_SHAPE;
+  const int units = sh->B * sh->Hkv, G = sh->Hq / sh->Hkv;
+  const int n_items = c->W_cap / kTile + c->n_q / kTile;
+  if (n_splits < 0 || n_splits > max_splits(sh)) return KVMIX_ERR_BAD_SHAPE;
+  if (n_splits == 0) {
+    // enough workgroups to give every CU two, each with at least 8 tiles of work
+    n_splits = (512 + units - 1) / units;
+    if (n_splits > n_items / 8) n_splits = n_items / 8;
+    if (n_splits > max_splits(sh)) n_splits = max_splits(sh);
+    if (n_splits < 1) n_splits = 1;
+  }
+  if (n_splits > n_items) n_splits = n_items;
+  AttnArgs a{};
+  if (n_splits > 1) {
+    if (!workspace) return KVMIX_ERR_NULL;
+    if (!aligned16(workspace)) return KVMIX_ERR_ALIGN;
+    const size_t need = counters_bytes(units) + (size_t)units * n_splits * G * (kD + 2) * sizeof(float);
+    if (workspace_bytes < need) return KVMIX_ERR_WORKSPACE;
+    a.counters = reinterpret_cast<uint32_t*>(workspace);
+    a.part = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) + counters_bytes(units));
+  }
+  a.q = q; a.out = out;
+  a.k_codes = c->k_codes; a.k_scale = c->k_scale; a.k_zero = c->k_zero;
+  a.v_codes = c->v_codes; a.v_scale = c->v_scale; a.v_zero = c->v_zero;
+  a.k_win = c->k_win; a.v_win = c->v_win;
+  a.tiles_cap = c->T_cap / kTile; a.W_cap = c->W_cap; a.n_tiles = c->n_q / kTile; a.n_w = c->n_w; a.w0 = c->w0;
+  a.Hq = sh->Hq; a.Hkv = sh->Hkv; a.n_splits = n_splits;
+  const float scale = softmax_scale > 0.0f ? softmax_scale : 1.0f / std::sqrt((float)kD);
+  a.scale_log2 = scale * 1.4426950408889634f;
+  const int kb = cfg->k_bits == 16 ? 2 : cfg->k_bits, vb = cfg->v_bits == 16 ? 2 : cfg->v_bits;
+  const hipError_t e = launch_decode_attn(a, kb, vb, G, units, (hipStream_t)stream);
+  return e == hipSuccess ? KVMIX_OK : hip_fail(e);
+}
+
+int kvmix_dequant(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const kvmix_layer_cache* c, int which, float* out, void* stream) {
+  int st = check_shape_cfg(sh, cfg);
+  if (st) return st;
+  if (cfg->k_bits == 16) return KVMIX_ERR_BAD_BITS;
+  if (!out) return KVMIX_ERR_NULL;
+  if (which != 0 && which != 1) return KVMIX_ERR_BAD_SHAPE;
+  st = check_cache(cfg, c, true);
+  if (st) return st;
+  DequantArgs a{};
+  a.codes = which ? c->v_codes : c->k_codes;
+  a.scale = which ? c->v_scale : c->k_scale;
+  a.zero = which ? c->v_zero : c->k_zero;
+  a.out = out; a.tiles_cap = c->T_cap / kTile; a.n_tiles = c->n_q / kTile;
+  a.bits = which ? cfg->v_bits : cfg->k_bits; a.which = which;
+  const hipError_t e = launch_dequant(a, sh->B * sh->Hkv, (hipStream_t)stream);
+  return e == hipSuccess ? KVMIX_OK : hip_fail(e);
+}
+
+}  // extern "C"

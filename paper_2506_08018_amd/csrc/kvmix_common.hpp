@@ -1,0 +1,97 @@
+// Shared definitions of the KVmix HIP library (gfx950). Not used by the CPU oracle.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "../../include/kvmix.h"
+
+namespace kvmix {
+
+constexpr int kD = 128;        // head dimension
+constexpr int kTile = 32;      // tokens per tile = Key group length = Value group width
+constexpr int kWave = 64;
+
+typedef _Float16 half_t;
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+__host__ __device__ constexpr int tile_words(int bits) { return 128 * bits; }  // 32 x 128 codes
+
+// Position of a code inside its tile (layout statement: include/kvmix.h).
+// (l, j, hh, slot): 16-byte column, word in column, 16-bit half, slot in half.
+struct CodePos { int word, bit, hword, hbit; };
+
+__host__ __device__ inline CodePos pos_from_slots(int bits, int l, int j, int hh, int slot) {
+  CodePos p;
+  p.hword = -1; p.hbit = 0;
+  if (bits == 4) {
+    p.word = 256 * (slot >> 2) + 4 * l + j;
+    p.bit = 16 * hh + 4 * (slot & 3);
+    return p;
+  }
+  p.word = 4 * l + j;
+  p.bit = 16 * hh + 2 * slot;
+  if (bits == 3) {
+    p.hword = 256 + 2 * l + (j >> 1);
+    p.hbit = 16 * hh + 8 * (j & 1) + 2 * (slot & 3) + (slot >> 2);
+  }
+  return p;
+}
+
+// Token / channel held by (column l, word j, half hh, slot) of a Key or Value tile.
+__host__ __device__ inline void key_td(int l, int j, int hh, int slot, int& tau, int& d) {
+  const int i = l & 15, kq = l >> 4, ks = slot & 3, m = slot >> 2;
+  d = 32 * ks + 8 * kq + 2 * j + hh;
+  tau = 8 * (i >> 2) + 4 * m + (i & 3);
+}
+__host__ __device__ inline void value_td(int l, int j, int hh, int slot, int& tau, int& d) {
+  const int i = l & 15, kq = l >> 4;
+  d = 16 * slot + i;
+  tau = 8 * kq + 2 * j + hh;
+}
+
+// Launch descriptors filled by the C-ABI layer (host) and passed by value.
+struct QuantArgs {
+  const uint16_t* k; const uint16_t* v;
+  int64_t k_tok, k_unit_b, k_unit_h;            // Key input: channel stride 1
+  int64_t v_tok, v_chan, v_unit_b, v_unit_h;    // Value input: channel stride 1 or token stride 1
+  uint32_t* k_codes; uint16_t* k_scale; uint16_t* k_zero;
+  uint32_t* v_codes; uint16_t* v_scale; uint16_t* v_zero;
+  int tiles_cap;   // tiles per unit in the packed cache
+  int tile0;       // first destination tile
+  int Hkv;
+};
+
+struct DequantArgs {
+  const uint32_t* codes; const uint16_t* scale; const uint16_t* zero;
+  float* out; int tiles_cap; int n_tiles; int bits; int which;
+};
+
+struct AppendArgs {
+  const uint16_t* k_new; const uint16_t* v_new;
+  uint16_t* k_win; uint16_t* v_win;
+  int W_cap; int slot; int units;
+};
+
+struct AttnArgs {
+  const uint16_t* q; uint16_t* out;
+  const uint32_t* k_codes; const uint16_t* k_scale; const uint16_t* k_zero;
+  const uint32_t* v_codes; const uint16_t* v_scale; const uint16_t* v_zero;
+  const uint16_t* k_win; const uint16_t* v_win;
+  float* part;            // split partials: [units][n_splits][G][kD + 2]
+  uint32_t* counters;     // [units] arrival counters (zero before and after every call)
+  int tiles_cap, W_cap, n_tiles, n_w, w0;
+  int Hq, Hkv, n_splits;
+  float scale_log2;       // softmax_scale * log2(e)
+};
+
+hipError_t launch_quantize_pack(const QuantArgs& a, int k_bits, int v_bits, bool v_token_contig,
+                                int n_tiles, int units, hipStream_t s);
+hipError_t launch_dequant(const DequantArgs& a, int units, hipStream_t s);
+hipError_t launch_append(const AppendArgs& a, hipStream_t s);
+hipError_t launch_decode_attn(const AttnArgs& a, int k_bits, int v_bits, int G, int units, hipStream_t s);
+int attn_threads();   // workgroup size of the attention kernel
+
+}  // namespace kvmix

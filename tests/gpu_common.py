@@ -1,0 +1,87 @@
+"""Helpers for the GPU parity tests: build the same cache on both sides from the same seeded inputs."""
+import numpy as np
+
+import kvmix_synth as synth
+from oracle.kvmix_ref import RefCache
+
+ATOL = 2e-3   # max-abs bound on fp16 attention outputs (spec tolerance)
+RTOL_L2 = 1e-2  # per-row relative L2 bound
+
+
+def u16(a):
+    return np.ascontiguousarray(a).view(np.uint16)
+
+
+def h2f64(a):
+    return np.asarray(a, np.uint16).view(np.float16).astype(np.float64)
+
+
+def t16(t):
+    """torch fp16 tensor -> numpy uint16 bits on the host."""
+    import torch
+    return t.detach().contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def bits_of(t, dtype):
+    """raw uint8 device buffer -> numpy array of `dtype` on the host."""
+    return t.cpu().numpy().view(dtype)
+
+
+def make_pair(B, Hq, Hkv, T, W, kb, vb, seed=0, layer=0, T_cap=None, W_cap=None, q_k_v=None):
+    """Seeded inputs; the oldest T - W' tokens packed (W' = W rounded so that n_q % 32 == 0), the rest
+    in the window. Returns (q, k, v numpy fp16, RefCache, gpu LayerCache, Shape, LayerCfg)."""
+    import torch
+    import paper_2506_08018_amd as kv
+    q, k, v = q_k_v if q_k_v is not None else synth.gen_layer_numpy(seed, layer, B, Hq, Hkv, T)
+    n_q = 0 if kb == 16 else max(0, (T - W) // 32 * 32)
+    n_w = T - n_q
+    T_cap = T_cap or max(n_q, 32)
+    W_cap = W_cap or ((n_w + 63) // 32) * 32
+    rc = RefCache(B, Hq, Hkv, kb, vb, W, T_cap, W_cap)
+    shape, cfg = kv.Shape(B, Hq, Hkv), kv.LayerCfg(kb, vb, W)
+    gc = kv.LayerCache(shape, cfg, T_cap, W_cap)
+    kt = torch.from_numpy(k).cuda()
+    vt = torch.from_numpy(v).cuda()
+    if n_q:
+        assert rc.quantize_pack(u16(k[:, :, :n_q]), u16(v[:, :, :n_q])) == 0
+        kv.quantize_pack(shape, cfg, kt[:, :, :n_q], vt[:, :, :n_q], gc)
+    rc.set_window(u16(k[:, :, n_q:]), u16(v[:, :, n_q:]))
+    gc.set_window(kt[:, :, n_q:], vt[:, :, n_q:])
+    return q, k, v, rc, gc, shape, cfg
+
+
+def assert_cache_equal(rc, gc, n_tiles=None):
+    """Bit-exact comparison of codes, scales and zero-points of the packed tiles."""
+    nt = rc.n_q // 32 if n_tiles is None else n_tiles
+    units = rc.units
+    for name, dt in (("k_codes", np.uint32), ("v_codes", np.uint32), ("k_scale", np.uint16), ("k_zero", np.uint16),
+                     ("v_scale", np.uint16), ("v_zero", np.uint16)):
+        want = getattr(rc, name)
+        got = bits_of(getattr(gc, name), dt)[: want.size].reshape(want.shape)
+        assert units == want.shape[0]
+        if not np.array_equal(got[:, :nt], want[:, :nt]):
+            bad = np.argwhere(got[:, :nt] != want[:, :nt])
+            raise AssertionError(f"{name}: {len(bad)} mismatching entries, first at {bad[0]}: got {got[:, :nt][tuple(bad[0])]:#x} want {want[:, :nt][tuple(bad[0])]:#x}")
+
+
+def assert_attn_close(got_bits, want_bits, what=""):
+    got, want = h2f64(got_bits), h2f64(want_bits)
+    assert np.all(np.isfinite(got)), f"{what}: non-finite output"
+    err = np.abs(got - want)
+    rows = want.reshape(-1, want.shape[-1])
+    rel = np.linalg.norm((got - want).reshape(rows.shape), axis=1) / np.maximum(np.linalg.norm(rows, axis=1), 1e-30)
+    assert err.max() <= ATOL, f"{what}: max abs err {err.max():.3e} > {ATOL}"
+    assert rel.max() <= RTOL_L2, f"{what}: max rel-L2 err {rel.max():.3e} > {RTOL_L2}"
+    return err.max(), rel.max()
+
+
+def run_attn(gc, shape, cfg, q, n_splits=0, softmax_scale=0.0):
+    import torch
+    import paper_2506_08018_amd as kv
+    qt = torch.from_numpy(q).cuda()
+    out = torch.zeros_like(qt)
+    ws = torch.zeros(kv.workspace_bytes(shape, gc.T_cap), dtype=torch.uint8, device="cuda")
+    kv.decode_attn(shape, cfg, qt, gc, out, ws, softmax_scale=softmax_scale, n_splits=n_splits)
+    torch.cuda.synchronize()
+    assert not ws[: 4 * shape.units].any(), "arrival counters not reset"
+    return t16(out)

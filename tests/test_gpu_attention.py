@@ -1,0 +1,157 @@
+"""GPU parity: kvmix_decode_attn / kvmix_append vs the oracle (max-abs 2e-3, per-row rel-L2 1e-2)."""
+import numpy as np
+import pytest
+
+import kvmix_synth as synth
+from gpu_common import assert_attn_close, assert_cache_equal, bits_of, make_pair, run_attn, t16, u16
+
+pytestmark = pytest.mark.gpu
+
+COMBOS = [(kb, vb) for kb in (2, 3, 4) for vb in (2, 3, 4)]
+
+
+@pytest.mark.parametrize("kb,vb", COMBOS)
+@pytest.mark.parametrize("G", [1, 4])
+def test_all_bit_combos(kb, vb, G):
+    print(f"case attn kb={kb} vb={vb} G={G}", flush=True)
+    B, Hkv, T, W = 2, 2, 32 * 9 + 17, 32            # ragged window: n_w = 49
+    q, k, v, rc, gc, shape, cfg = make_pair(B, Hkv * G, Hkv, T, W, kb, vb, seed=200 + kb * 10 + vb)
+    st, want = rc.decode_attn(u16(q))
+    assert st == 0
+    got = run_attn(gc, shape, cfg, q)
+    assert_attn_close(got, want, f"kb={kb} vb={vb} G={G}")
+
+
+@pytest.mark.parametrize("G", [1, 2, 4, 8])
+def test_gqa_groups_and_scale(G):
+    print(f"case gqa G={G}", flush=True)
+    q, k, v, rc, gc, shape, cfg = make_pair(1, 2 * G, 2, 32 * 20 + 40, 32, 2, 4, seed=300 + G)
+    for scale in (0.0, 0.05):
+        st, want = rc.decode_attn(u16(q), scale)
+        got = run_attn(gc, shape, cfg, q, softmax_scale=scale)
+        assert_attn_close(got, want, f"G={G} scale={scale}")
+
+
+@pytest.mark.parametrize("n_splits", [1, 2, 3, 5, 8])
+def test_result_independent_of_split_count(n_splits):
+    print(f"case splits={n_splits}", flush=True)
+    q, k, v, rc, gc, shape, cfg = make_pair(2, 8, 2, 32 * 33 + 5, 64, 3, 4, seed=400)
+    st, want = rc.decode_attn(u16(q))
+    got = run_attn(gc, shape, cfg, q, n_splits=n_splits)
+    assert_attn_close(got, want, f"splits={n_splits}")
+    again = run_attn(gc, shape, cfg, q, n_splits=n_splits)   # counters were reset: second call still right
+    assert_attn_close(again, want, f"splits={n_splits} (second call)")
+
+
+@pytest.mark.parametrize("kb,vb,G", [(16, 16, 1), (16, 16, 4), (2, 2, 2)])
+def test_window_only_is_exact_fp_attention(kb, vb, G):
+    """16-bit setting / window covering the context: no packed tokens at all."""
+    print(f"case window-only kb={kb} G={G}", flush=True)
+    T = 200
+    q, k, v, rc, gc, shape, cfg = make_pair(2, 2 * G, 2, T, 256, kb, vb, seed=500)
+    assert gc.n_q == 0 and gc.n_w == T
+    st, want = rc.decode_attn(u16(q))
+    got = run_attn(gc, shape, cfg, q)
+    err, _ = assert_attn_close(got, want, "window-only")
+    assert err <= 2.0 ** -10 * np.abs(q).max() * 4   # fp32 accumulation: at most an fp16 ulp or two off
+
+
+def test_edge_contexts():
+    """Single-token context; packed tokens only (empty window); exactly one packed tile."""
+    import torch
+    print("case single token", flush=True)
+    q, k, v, rc, gc, shape, cfg = make_pair(1, 2, 2, 1, 32, 16, 16, seed=600)
+    st, want = rc.decode_attn(u16(q))
+    got = run_attn(gc, shape, cfg, q)
+    assert np.array_equal(got, want) and np.array_equal(got[0], u16(v[0, :, 0]))
+    print("case empty window", flush=True)
+    q, k, v, rc, gc, shape, cfg = make_pair(1, 4, 2, 96, 0, 2, 3, seed=601)
+    assert gc.n_w == 0 and gc.n_q == 96
+    st, want = rc.decode_attn(u16(q))
+    assert st == 0
+    assert_attn_close(run_attn(gc, shape, cfg, q), want, "empty window")
+    print("case one tile", flush=True)
+    q, k, v, rc, gc, shape, cfg = make_pair(1, 2, 2, 33, 0, 4, 4, seed=602)
+    assert gc.n_q == 32 and gc.n_w == 1
+    st, want = rc.decode_attn(u16(q))
+    assert_attn_close(run_attn(gc, shape, cfg, q), want, "one tile")
+
+
+def test_sharp_softmax_and_large_values():
+    """(a) queries aligned with one packed / one window key (softmax close to one-hot);
+    (b) Values of magnitude ~10, where the fp16 output spacing exceeds the absolute bound."""
+    from gpu_common import h2f64
+    B, Hkv, G, T, W = 1, 2, 2, 32 * 12 + 32, 32
+    print("case sharp softmax", flush=True)
+    q, k, v = synth.gen_layer_numpy(700, 0, B, Hkv * G, Hkv, T)
+    q[0, 0] = (k[0, 0, 77].astype(np.float32) * 0.4).astype(np.float16)
+    q[0, 3] = (k[0, 1, T - 5].astype(np.float32) * 0.4).astype(np.float16)
+    _, _, _, rc, gc, shape, cfg = make_pair(B, Hkv * G, Hkv, T, W, 2, 2, q_k_v=(q, k, v))
+    st, want = rc.decode_attn(u16(q))
+    assert_attn_close(run_attn(gc, shape, cfg, q), want, "sharp softmax")
+    print("case large values", flush=True)
+    q, k, v = synth.gen_layer_numpy(701, 0, B, Hkv * G, Hkv, T)
+    v = (v.astype(np.float32) * 4.0).astype(np.float16)
+    _, _, _, rc, gc, shape, cfg = make_pair(B, Hkv * G, Hkv, T, W, 2, 2, q_k_v=(q, k, v))
+    st, want = rc.decode_attn(u16(q))
+    got = run_attn(gc, shape, cfg, q)
+    err = np.abs(h2f64(got) - h2f64(want))
+    big = np.maximum(np.abs(h2f64(want)), np.abs(h2f64(got)))
+    ulp = 2.0 ** (np.floor(np.log2(np.maximum(big, 2.0 ** -14))) - 10)
+    # outputs above 2 have an fp16 spacing wider than the absolute bound: allow one spacing there
+    bad = np.argwhere(err > np.maximum(2e-3, 1.01 * ulp))
+    assert len(bad) == 0, [(tuple(i), h2f64(want)[tuple(i)], h2f64(got)[tuple(i)]) for i in bad[:5]]
+
+
+@pytest.mark.parametrize("kb,vb,G", [(2, 2, 1), (3, 4, 4)])
+def test_append_and_flush_match_oracle(kb, vb, G):
+    """Token-by-token appends through the ring window, flushing 32 aged tokens at a time, on both sides."""
+    import torch
+    import paper_2506_08018_amd as kv
+    print(f"case append kb={kb} vb={vb} G={G}", flush=True)
+    B, Hkv, W, T0, steps = 2, 2, 32, 96, 75
+    q, k, v = synth.gen_layer_numpy(800, 0, B, Hkv * G, Hkv, T0 + steps)
+    _, _, _, rc, gc, shape, cfg = make_pair(B, Hkv * G, Hkv, T0, W, kb, vb, T_cap=256, W_cap=64, q_k_v=(q, k[:, :, :T0], v[:, :, :T0]))
+    kt, vt = torch.from_numpy(k).cuda(), torch.from_numpy(v).cuda()
+    for s in range(steps):
+        assert rc.append(u16(k[:, :, T0 + s]), u16(v[:, :, T0 + s])) == 0
+        kv.append(shape, cfg, kt[:, :, T0 + s].contiguous(), vt[:, :, T0 + s].contiguous(), gc)
+        assert (gc.n_q, gc.n_w, gc.w0) == (rc.n_q, rc.n_w, rc.w0)
+        if s in (0, 31, 32, 33, 74):
+            st, want = rc.decode_attn(u16(q))
+            assert_attn_close(run_attn(gc, shape, cfg, q), want, f"after append {s}")
+    torch.cuda.synchronize()
+    assert_cache_equal(rc, gc)
+    assert np.array_equal(bits_of(gc.k_win, np.uint16).reshape(rc.k_win.shape), rc.k_win)
+    assert np.array_equal(bits_of(gc.v_win, np.uint16).reshape(rc.v_win.shape), rc.v_win)
+
+
+def test_config1_full_parity():
+    """BASELINE config 1 in full: 1 layer, B1, 32 heads, T1024, window 32, K2/V2."""
+    print("case config1", flush=True)
+    c = synth.CONFIGS["cfg1_single_layer"]
+    q, k, v, rc, gc, shape, cfg = make_pair(c["B"], c["Hq"], c["Hkv"], c["T"], c["W"], 2, 2, seed=synth.BASE_SEED)
+    assert gc.n_q == 992 and gc.n_w == 32
+    assert_cache_equal(rc, gc)
+    st, want = rc.decode_attn(u16(q))
+    for ns in (0, 1, 4):
+        assert_attn_close(run_attn(gc, shape, cfg, q, n_splits=ns), want, f"config1 splits={ns}")
+
+
+def test_attn_error_returns():
+    import torch
+    import paper_2506_08018_amd as kv
+    q, k, v, rc, gc, shape, cfg = make_pair(1, 2, 2, 96, 32, 2, 2, seed=1)
+    qt = torch.from_numpy(q).cuda()
+    out = torch.zeros_like(qt)
+    with pytest.raises(kv.KVMixError) as e:      # splits > 1 without workspace
+        kv.decode_attn(shape, cfg, qt, gc, out, None, n_splits=2)
+    assert e.value.status == -1
+    small = torch.zeros(64, dtype=torch.uint8, device="cuda")
+    with pytest.raises(kv.KVMixError) as e:
+        kv.decode_attn(shape, cfg, qt, gc, out, small, n_splits=2)
+    assert e.value.status == -6
+    with pytest.raises(kv.KVMixError) as e:      # G = 3 unsupported
+        kv.decode_attn(kv.Shape(1, 6, 2), cfg, qt, gc, out, None)
+    assert e.value.status == -4
+    assert not out.any()
