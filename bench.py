@@ -1,0 +1,201 @@
+#!/usr/bin/env python3
+"""Benchmark of the KVmix hot path on one MI355X.
+
+One "step" = one decode step of the whole hot path over all layers of the workload: per layer,
+append the new token's K/V to the fp16 window (flushing 32 aged tokens through quantize-and-pack
+when the window overflows) and run the fused mixed-bit decode attention. Inputs are synthetic
+(kvmix_synth) and resident in HBM before the timed region.
+
+Prints ONE JSON line: throughput in decode tokens/s, the HBM roofline of the attention kernel
+(algorithmic bytes per launch / average launch duration, measured with events on the launch
+stream over an attention-only timed region), and the CPU oracle timed on a bounded sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import kvmix_synth as synth  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0
+# HBM bytes per attention launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/); None = not measured
+MEASURED_TRAFFIC_BYTES = None
+
+
+def algorithmic_bytes(units, n_q, n_w, kb, vb):
+    """Bytes the method itself must move for one layer's decode attention (D = 128, group 32):
+    packed token: 16*bK + 16*bV code bytes + 32 bytes of fp16 scale/min; window token: 512 bytes."""
+    return units * (n_q * (16 * kb + 16 * vb + 32) + n_w * 512)
+
+
+def build_layers(cfg, device, seed):
+    import torch
+    import paper_2506_08018_amd as kv
+    L, B, Hq, Hkv, T, W = cfg["L"], cfg["B"], cfg["Hq"], cfg["Hkv"], cfg["T"], cfg["W"]
+    kbits, vbits = synth.bit_table(L, seed)
+    if cfg["bits"] == "2/2":
+        kbits[:], vbits[:] = 2, 2
+    shape = kv.Shape(B, Hq, Hkv)
+    # start 8 tokens short of T with 24 tokens above the window length, so that a flush of 32 aged tokens
+    # falls inside a short run and the context is T right after it
+    n_w0 = W + 24
+    n_q0 = T - 8 - n_w0
+    assert n_q0 % 32 == 0 and n_q0 >= 0
+    layers = []
+    for l in range(L):
+        lc = kv.LayerCfg(int(kbits[l]), int(vbits[l]), W)
+        cache = kv.LayerCache(shape, lc, T_cap=T + 64, W_cap=W + 32, device=device)
+        q, k, v = synth.gen_layer_torch(device, seed, l, B, Hq, Hkv, n_q0 + n_w0)
+        kv.quantize_pack(shape, lc, k[:, :, :n_q0], v[:, :, :n_q0], cache)
+        cache.set_window(k[:, :, n_q0:], v[:, :, n_q0:])
+        layers.append(dict(cfg=lc, cache=cache, q=q, out=torch.zeros_like(q)))
+        del k, v
+    torch.cuda.synchronize()
+    return shape, layers, kbits, vbits
+
+
+def cpu_baseline(cfg, seed, kbits, vbits, target_s=12.0):
+    """The oracle's decode attention (and quantize-pack) timed on the host cores for a bounded sample:
+    whole kv heads of layer 0 (same recipe, numpy stream), scaled linearly to the full workload
+    (units are independent)."""
+    from oracle import kvmix_ref
+    from oracle.kvmix_ref import RefCache
+    L, B, Hq, Hkv, T, W = cfg["L"], cfg["B"], cfg["Hq"], cfg["Hkv"], cfg["T"], cfg["W"]
+    G = Hq // Hkv
+    threads = kvmix_ref.num_threads()
+    n_units = max(threads, 8)
+    total_units = L * B * Hkv
+    Hs = min(Hkv, n_units)
+    Bs = max(1, min(B, n_units // Hs))
+    n_q = (T - W) // 32 * 32
+    q, k, v = synth.gen_layer_numpy(seed, 0, Bs, Hs * G, Hs, T)
+    u16 = lambda a: np.ascontiguousarray(a).view(np.uint16)
+    t_attn, t_qp, reps = 0.0, 0.0, 0
+    while t_attn < target_s and reps < 1000:
+        rc = RefCache(Bs, Hs * G, Hs, int(kbits[0]), int(vbits[0]), W, n_q, W + 32)
+        t0 = time.perf_counter()
+        rc.quantize_pack(u16(k[:, :, :n_q]), u16(v[:, :, :n_q]))
+        t1 = time.perf_counter()
+        rc.set_window(u16(k[:, :, n_q:]), u16(v[:, :, n_q:]))
+        t2 = time.perf_counter()
+        st, _ = rc.decode_attn(u16(q))
+        t3 = time.perf_counter()
+        assert st == 0
+        t_qp += t1 - t0
+        t_attn += t3 - t2
+        reps += 1
+    per_unit = t_attn / (reps * Bs * Hs)
+    step_s = per_unit * total_units
+    return {
+        "value": B / step_s, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+        "sample": f"decode attention of {Bs * Hs} of {total_units} (layer,batch,kv-head) units (layer 0 bits "
+                  f"K{int(kbits[0])}/V{int(vbits[0])}, context {T}), {reps} repetitions, {t_attn:.1f} s of CPU time, scaled "
+                  f"linearly to all units; OpenMP over units",
+        "quantize_pack_tokens_per_s": (reps * Bs * Hs * n_q) / t_qp,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="cfg2_llama2_7b", choices=sorted(synth.CONFIGS))
+    ap.add_argument("--seed", type=int, default=synth.BASE_SEED)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--n-splits", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (every unit = (layer, batch, kv head) is independent; "
+                 "see DESIGN.md for how the path shards). Use --gpus 1.")
+
+    import torch
+    import paper_2506_08018_amd as kv
+    kv.lib()  # fail loudly if the HIP library is missing
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    device = torch.device("cuda:0")
+    torch.cuda.set_device(device)
+
+    cfg = synth.CONFIGS[args.config]
+    L, B, Hq, Hkv = cfg["L"], cfg["B"], cfg["Hq"], cfg["Hkv"]
+    units = B * Hkv
+    shape, layers, kbits, vbits = build_layers(cfg, device, args.seed)
+    ws = torch.zeros(kv.workspace_bytes(shape, cfg["T"] + 64), dtype=torch.uint8, device=device)
+    g = torch.Generator(device=device)
+    g.manual_seed(args.seed + 77)
+    n_new = args.steps + args.warmup + 1
+    k_new = torch.randn((n_new, L, B, Hkv, 128), generator=g, device=device, dtype=torch.float32).to(torch.float16)
+    v_new = torch.randn((n_new, L, B, Hkv, 128), generator=g, device=device, dtype=torch.float32).to(torch.float16)
+
+    def step(i):
+        nbytes = 0
+        for l, ly in enumerate(layers):
+            kv.append(shape, ly["cfg"], k_new[i, l], v_new[i, l], ly["cache"])
+            kv.decode_attn(shape, ly["cfg"], ly["q"], ly["cache"], ly["out"], ws, n_splits=args.n_splits)
+            nbytes += algorithmic_bytes(units, ly["cache"].n_q, ly["cache"].n_w, ly["cfg"].k_bits, ly["cfg"].v_bits)
+        return nbytes
+
+    def attn_only():
+        for ly in layers:
+            kv.decode_attn(shape, ly["cfg"], ly["q"], ly["cache"], ly["out"], ws, n_splits=args.n_splits)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    total_bytes = 0
+    for i in range(args.warmup, args.warmup + args.steps):
+        total_bytes += step(i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / args.steps * 1e3
+
+    # attention-only timed region: average launch duration of the dominant kernel, events on the launch stream
+    attn_only()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        attn_only()
+    e1.record()
+    torch.cuda.synchronize()
+    attn_ms = e0.elapsed_time(e1) / args.steps
+    launch_us = attn_ms * 1e3 / L
+    layer_bytes = [algorithmic_bytes(units, ly["cache"].n_q, ly["cache"].n_w, ly["cfg"].k_bits, ly["cfg"].v_bits) for ly in layers]
+    bytes_per_launch = float(np.mean(layer_bytes))
+    achieved = bytes_per_launch / (launch_us * 1e-6) / 1e9
+
+    result = {
+        "metric": "decode-attn tokens/s over mixed-bit KV; achieved HBM GB/s vs MI355X peak",
+        "value": B * args.steps / elapsed,
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16 in / f32 accumulate (2-4 bit integer codes)", "data": "synthetic",
+        "config": {"workload": args.config, "layers": L, "batch": B, "q_heads": Hq, "kv_heads": Hkv, "head_dim": 128,
+                   "context": cfg["T"], "window": cfg["W"], "group": 32,
+                   "mean_k_bits": float(np.mean(kbits)), "mean_v_bits": float(np.mean(vbits)), "seed": args.seed,
+                   "step": "per layer: kvmix_append (1 token, flush of 32 when due) + kvmix_decode_attn",
+                   "packed_cache_bytes": int(sum(ly["cache"].nbytes() for ly in layers))},
+        "step_hbm_gbs": total_bytes / elapsed / 1e9,
+        "attn_only_ms_per_step": attn_ms,
+        "attn_only_tokens_per_s": B / (attn_ms * 1e-3),
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES,
+                     "kernel": "decode_attn_kernel", "bytes_per_launch": bytes_per_launch, "launch_us": launch_us,
+                     "launches_timed": args.steps * L},
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg, args.seed, kbits, vbits)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()
