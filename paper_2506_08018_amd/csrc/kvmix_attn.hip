@@ -11,10 +11,15 @@
 // exact, and MFMA honours subnormal inputs. The scale factors ride in the B operand, split
 // into an fp16 (hi, lo) pair held in two MFMA columns so that the products stay exact to
 // ~22 bits; the up-to-8 query heads of the group use columns 0..7 (hi) and 8..15 (lo).
-// The zero-point sums and the fp16 window are MFMAs on plain fp16 operands. Softmax is online,
-// per wave, with a lazily raised reference maximum; waves of a workgroup take tiles from a
-// shared counter and merge through LDS; splits of one unit merge through a workspace, the last
-// arriving workgroup writes the output.
+// The zero-point sums and the fp16 window are MFMAs on plain fp16 operands.
+//
+// Data movement. Every byte of a tile is loaded from HBM once, by one lane (16 B of codes,
+// 4 B of each scale / zero array per lane), several tiles ahead of its use. The scale-folded
+// B operands are computed cooperatively (each lane two values per head) and redistributed
+// through a wave-private LDS area, so no barrier is needed inside the main loop.
+// Softmax is online, per wave, with a lazily raised reference maximum; waves of a workgroup
+// take tiles from a shared counter and merge through LDS; splits of one unit merge through a
+// workspace, the last arriving workgroup writes the output.
 #include "kvmix_common.hpp"
 
 namespace kvmix {
@@ -23,7 +28,10 @@ namespace {
 
 constexpr int kWaves = 8;
 constexpr int kThreads = kWaves * kWave;
+constexpr int kDepth = 3;            // tiles in flight per wave
 constexpr float kRefMargin = 4.0f;   // reference maximum is raised to (tile max + margin), log2 units
+
+typedef float float2_t __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ float4_t mfma16(half8_t a, half8_t b, float4_t c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
@@ -33,6 +41,13 @@ __device__ __forceinline__ float ror8(float v) {
   return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x128, 0xf, 0xf, false));
 }
 __device__ __forceinline__ half8_t as_half8(u32x4_t v) { return __builtin_bit_cast(half8_t, v); }
+// orders the wave's own LDS writes before its following LDS reads (LDS executes a wave's
+// operations in order; this only pins the compiler)
+__device__ __forceinline__ void wave_lds_fence() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
 
 // bit position (inside a 16-bit half, after the unpack shift) of the field that feeds slot
 // `s` (0..3 = slot % 4): the MFMA sees code * 2^(pos - 24).
@@ -70,44 +85,91 @@ __device__ __forceinline__ void shift_hi_plane(const u32x2_t& h, u32x2_t (&hs)[4
   hs[3] = h >> 7;   // (1, 1):                 source bit 2*s + 9 -> 2*s + 2
 }
 
-template <int BITS> struct Codes;   // the lane's share of one packed tile
-template <> struct Codes<2> {
-  u32x4_t w, w8;
-  __device__ __forceinline__ void load(const uint32_t* tile, int lane) {
-    w = *reinterpret_cast<const u32x4_t*>(tile + 4 * lane);
-  }
-  __device__ __forceinline__ void prep() { w8 = w >> 8; }
-  __device__ __forceinline__ half8_t lo(int slot) const { return unpack2(w, w8, slot); }
+// The lane's share of one packed tile as loaded (Raw) and prepared for unpacking (Codes).
+template <int BITS> struct Raw;
+template <> struct Raw<2> {
+  u32x4_t w;
+  __device__ __forceinline__ void load(const uint32_t* tile, int lane) { w = *reinterpret_cast<const u32x4_t*>(tile + 4 * lane); }
 };
-template <> struct Codes<3> {
-  u32x4_t w, w8; u32x2_t h; u32x2_t hs[4];
+template <> struct Raw<3> {
+  u32x4_t w; u32x2_t h;
   __device__ __forceinline__ void load(const uint32_t* tile, int lane) {
     w = *reinterpret_cast<const u32x4_t*>(tile + 4 * lane);
     h = *reinterpret_cast<const u32x2_t*>(tile + 256 + 2 * lane);
   }
-  __device__ __forceinline__ void prep() { w8 = w >> 8; shift_hi_plane(h, hs); }
+};
+template <> struct Raw<4> {
+  u32x4_t w[2];
+  __device__ __forceinline__ void load(const uint32_t* tile, int lane) {
+    w[0] = *reinterpret_cast<const u32x4_t*>(tile + 4 * lane);
+    w[1] = *reinterpret_cast<const u32x4_t*>(tile + 256 + 4 * lane);
+  }
+};
+template <int BITS> struct Codes;
+template <> struct Codes<2> {
+  u32x4_t w, w8;
+  __device__ __forceinline__ explicit Codes(const Raw<2>& r) : w(r.w), w8(r.w >> 8) {}
+  __device__ __forceinline__ half8_t lo(int slot) const { return unpack2(w, w8, slot); }
+};
+template <> struct Codes<3> {
+  u32x4_t w, w8; u32x2_t hs[4];
+  __device__ __forceinline__ explicit Codes(const Raw<3>& r) : w(r.w), w8(r.w >> 8) { shift_hi_plane(r.h, hs); }
   __device__ __forceinline__ half8_t lo(int slot) const { return unpack2(w, w8, slot); }
   __device__ __forceinline__ half8_t hi(int slot) const { return unpack1(hs, slot); }
 };
 template <> struct Codes<4> {
   u32x4_t w[2], w8[2];
-  __device__ __forceinline__ void load(const uint32_t* tile, int lane) {
-    w[0] = *reinterpret_cast<const u32x4_t*>(tile + 4 * lane);
-    w[1] = *reinterpret_cast<const u32x4_t*>(tile + 256 + 4 * lane);
-  }
-  __device__ __forceinline__ void prep() { w8[0] = w[0] >> 8; w8[1] = w[1] >> 8; }
+  __device__ __forceinline__ explicit Codes(const Raw<4>& r) { w[0] = r.w[0]; w[1] = r.w[1]; w8[0] = r.w[0] >> 8; w8[1] = r.w[1] >> 8; }
   __device__ __forceinline__ half8_t lo(int slot) const { return unpack4(w[slot >> 2], w8[slot >> 2], slot & 3); }
 };
 
-// fp32 value -> the lane's part of its fp16 (hi, lo) split
+// One tile in flight: codes plus the lane's two scales / zero-points of each array.
+template <int KB, int VB> struct Stage {
+  Raw<KB> kc; Raw<VB> vc;
+  uint32_t ks, kz, vs, vz;
+  __device__ __forceinline__ void load(const AttnArgs& a, size_t tile, int lane) {
+    kc.load(a.k_codes + tile * tile_words(KB), lane);
+    ks = reinterpret_cast<const uint32_t*>(a.k_scale + tile * kD)[lane];
+    kz = reinterpret_cast<const uint32_t*>(a.k_zero + tile * kD)[lane];
+    vc.load(a.v_codes + tile * tile_words(VB), lane);
+    vs = reinterpret_cast<const uint32_t*>(a.v_scale + tile * kD)[lane];
+    vz = reinterpret_cast<const uint32_t*>(a.v_zero + tile * kD)[lane];
+  }
+};
+
+__device__ __forceinline__ void st_agent(float* p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ float ld_agent(const float* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+
+// fp32 pair -> packed fp16 pairs (hi, lo) with hi + lo == x to ~22 bits
+__device__ __forceinline__ void split_pair(float x0, float x1, uint32_t& hi, uint32_t& lo) {
+  const half_t h0 = (half_t)x0, h1 = (half_t)x1;
+  const half_t l0 = (half_t)(x0 - (float)h0), l1 = (half_t)(x1 - (float)h1);
+  const half2_t hv = {h0, h1}, lv = {l0, l1};
+  hi = __builtin_bit_cast(uint32_t, hv);
+  lo = __builtin_bit_cast(uint32_t, lv);
+}
 __device__ __forceinline__ half_t split_part(float x, bool lo_part) {
   const half_t hi = (half_t)x;
   const half_t lo = (half_t)(x - (float)hi);
   return lo_part ? lo : hi;
 }
+__device__ __forceinline__ float lo_half(uint32_t v) { return (float)__builtin_bit_cast(half_t, (uint16_t)(v & 0xffffu)); }
+__device__ __forceinline__ float hi_half(uint32_t v) { return (float)__builtin_bit_cast(half_t, (uint16_t)(v >> 16)); }
+
+// Wave-private LDS exchange area (row pitches chosen so that the 16 columns of a 16-byte
+// operand read fall into distinct banks).
+struct __attribute__((aligned(16))) WaveLds {
+  uint16_t bk[16][kD + 8];   // scale-folded query, column-major: [column][channel], pitch 272 B
+  uint16_t zk[kD];           // Key zero-points of the tile
+  float p[8][kTile];         // softmax numerators [head][token]
+  uint16_t bv[4][16][kTile + 8];  // scale-folded probabilities [channel block][column][token], pitch 80 B
+  uint16_t pb[16][kTile + 8];     // probabilities split hi/lo [column][token]
+  uint16_t zv[4][kTile];     // Value zero-points [channel block][token]
+};
 
 template <int KB, int VB, int G>
 __global__ __launch_bounds__(kThreads) void decode_attn_kernel(AttnArgs a) {
+  __shared__ WaveLds lds_all[kWaves];
   __shared__ int s_next;
   __shared__ int s_last;
   __shared__ float red_o[kWaves][G][kD];
@@ -121,27 +183,44 @@ __global__ __launch_bounds__(kThreads) void decode_attn_kernel(AttnArgs a) {
   const bool col_valid = h < G;
   const int sp = blockIdx.x, u = blockIdx.y;
   const int b = u / a.Hkv, jh = u % a.Hkv;
+  WaveLds& L = lds_all[wave];
 
+  // work items of this split: window tiles first, then packed tiles
   const int n_wt = a.W_cap / kTile;
   const int n_items = n_wt + a.n_tiles;
   const int item_begin = (int)(((long long)sp * n_items) / a.n_splits);
   const int item_end = (int)(((long long)(sp + 1) * n_items) / a.n_splits);
-  if (tid == 0) s_next = item_begin;
+  const int win_begin = item_begin < n_wt ? item_begin : n_wt;
+  const int win_end = item_end < n_wt ? item_end : n_wt;
+  const int p_begin = (item_begin > n_wt ? item_begin : n_wt) - n_wt;
+  const int p_end = (item_end > n_wt ? item_end : n_wt) - n_wt;
+  if (tid == 0) s_next = p_begin;
+
+  // zero the exchange area: rows of unused columns stay zero for the whole kernel
+  {
+    u32x4_t* z = reinterpret_cast<u32x4_t*>(&L);
+    for (int i = lane; i < (int)(sizeof(WaveLds) / 16); i += kWave) z[i] = u32x4_t{0, 0, 0, 0};
+  }
   __syncthreads();
 
-  // query operands: B columns hold q of head h in the hi column, zero elsewhere
-  half8_t qB[4];
-  float qf[4][8];    // fp32 q, prescaled by 2^-field_pos for the code products
+  // query operands
+  half8_t qB[4];      // plain q as B operand: hi columns hold head h, everything else zero
+  float qc[G][2];     // q of channels (2*lane, 2*lane+1), prescaled by 2^-field_pos of the lane's channel block
   {
-    const uint16_t* qp = a.q + ((size_t)b * a.Hq + (size_t)jh * G + h) * kD;
+    const uint16_t* qbase = a.q + ((size_t)b * a.Hq + (size_t)jh * G) * kD;
+    const half8_t zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
     for (int ks = 0; ks < 4; ks++) {
-      half8_t v = {0, 0, 0, 0, 0, 0, 0, 0};
-      if (col_valid) v = *reinterpret_cast<const half8_t*>(qp + 32 * ks + 8 * kq);
+      half8_t v = zero8;
+      if (col_valid && !lo_part) v = *reinterpret_cast<const half8_t*>(qbase + (size_t)h * kD + 32 * ks + 8 * kq);
+      qB[ks] = v;
+    }
+    const float pre = __builtin_ldexpf(1.0f, -field_pos<KB>(lane >> 4));
 #pragma unroll
-      for (int e = 0; e < 8; e++) qf[ks][e] = (float)v[e] * __builtin_ldexpf(1.0f, -field_pos<KB>(ks));
-      const half8_t zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
-      qB[ks] = lo_part ? zero8 : v;
+    for (int hh = 0; hh < G; hh++) {
+      const uint32_t v = reinterpret_cast<const uint32_t*>(qbase + (size_t)hh * kD)[lane];
+      qc[hh][0] = lo_half(v) * pre;
+      qc[hh][1] = hi_half(v) * pre;
     }
   }
 
@@ -154,61 +233,107 @@ __global__ __launch_bounds__(kThreads) void decode_attn_kernel(AttnArgs a) {
   for (int m = 0; m < 8; m++) acc[m] = float4_t{0, 0, 0, 0};
   float mref = -INFINITY, lsum = 0.0f;
 
-  const size_t tile_base = (size_t)u * a.tiles_cap;
-
-  for (;;) {
-    int item = 0;
-    if (lane == 0) item = atomicAdd(&s_next, 1);
-    item = __builtin_amdgcn_readfirstlane(item);
-    if (item >= item_end) break;
-
-    float x[8];            // log2-domain scores of tokens 8*kq + e of this tile, column col
-    const bool is_window = item < n_wt;
-    int slot0 = 0;
-    size_t tile = 0;
-
-    if (is_window) {
-      slot0 = item * kTile;
-      // validity of the lane's 8 slots in the ring
-      bool any_valid = false;
-      {
-        const int first = (slot0 - a.w0 + a.W_cap) % a.W_cap;   // ring rank of the tile's first slot
-        any_valid = first < a.n_w;                               // w0 and tiles are 32-aligned
-      }
-      if (!any_valid) continue;
-      const uint16_t* kw = a.k_win + ((size_t)u * a.W_cap + slot0) * kD;
-      float4_t S[2] = {float4_t{0, 0, 0, 0}, float4_t{0, 0, 0, 0}};
+  // online softmax of the lane's 8 scores (tokens 8*kq + e of the tile, column col): raises the
+  // reference if needed (rescaling the accumulators) and returns the numerators
+  auto softmax_tile = [&](float (&x)[8], float (&p)[8]) {
 #pragma unroll
-      for (int m = 0; m < 2; m++) {
-        const int tau = 8 * (col >> 2) + 4 * m + (col & 3);   // row `col` of M-tile m
+    for (int e = 0; e < 8; e++) x[e] = x[e] + ror8(x[e]);   // hi column + lo column
+    float mx = x[0];
 #pragma unroll
-        for (int ks = 0; ks < 4; ks++) {
-          const half8_t A = *reinterpret_cast<const half8_t*>(kw + (size_t)tau * kD + 32 * ks + 8 * kq);
-          S[m] = mfma16(A, qB[ks], S[m]);
-        }
-      }
+    for (int e = 1; e < 8; e++) mx = fmaxf(mx, x[e]);
+    if (__any(mx > mref)) {
+      mx = fmaxf(mx, __shfl_xor(mx, 16));
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const float mnew = mx > mref ? mx + kRefMargin : mref;
+      const float f = (mnew == mref) ? 1.0f : __builtin_exp2f(mref - mnew);
+      mref = mnew;
+      lsum *= f;
+      accZ *= f;
 #pragma unroll
-      for (int m = 0; m < 2; m++)
+      for (int m = 0; m < 8; m++) acc[m] *= f;
+    }
+#pragma unroll
+    for (int e = 0; e < 8; e++) {
+      p[e] = col_valid ? __builtin_exp2f(x[e] - mref) : 0.0f;
+      lsum += p[e];
+    }
+  };
+
+  // ---- fp16 window tiles (few): taken round-robin by the waves before the packed stream
+  for (int wi = win_begin + wave; wi < win_end; wi += kWaves) {
+    const int slot0 = wi * kTile;
+    const int first = (slot0 - a.w0 + a.W_cap) % a.W_cap;   // ring rank of the tile's first slot
+    if (first >= a.n_w) continue;                            // w0 and tiles are 32-aligned
+    const uint16_t* kw = a.k_win + ((size_t)u * a.W_cap + slot0) * kD;
+    const uint16_t* vw = a.v_win + (size_t)u * kD * a.W_cap + slot0 + 8 * kq;
+    half8_t Ak[2][4], Av[8];
+#pragma unroll
+    for (int m = 0; m < 2; m++) {
+      const int tau = 8 * (col >> 2) + 4 * m + (col & 3);   // row `col` of M-tile m
+#pragma unroll
+      for (int ks = 0; ks < 4; ks++) Ak[m][ks] = *reinterpret_cast<const half8_t*>(kw + (size_t)tau * kD + 32 * ks + 8 * kq);
+    }
+#pragma unroll
+    for (int m = 0; m < 8; m++) Av[m] = *reinterpret_cast<const half8_t*>(vw + (size_t)(16 * m + col) * a.W_cap);
+    float4_t S[2] = {float4_t{0, 0, 0, 0}, float4_t{0, 0, 0, 0}};
+#pragma unroll
+    for (int m = 0; m < 2; m++)
+#pragma unroll
+      for (int ks = 0; ks < 4; ks++) S[m] = mfma16(Ak[m][ks], qB[ks], S[m]);
+    float x[8], p[8];
+#pragma unroll
+    for (int m = 0; m < 2; m++)
+#pragma unroll
+      for (int r = 0; r < 4; r++) x[4 * m + r] = (first + 8 * kq + 4 * m + r) < a.n_w ? S[m][r] * c_plain : -INFINITY;
+    softmax_tile(x, p);
+    half8_t PB;
+#pragma unroll
+    for (int e = 0; e < 8; e++) PB[e] = split_part(p[e], lo_part);
+#pragma unroll
+    for (int m = 0; m < 8; m++) {
+      float4_t t = mfma16(Av[m], PB, float4_t{0, 0, 0, 0});
+      if constexpr (VB == 3) {   // the final 7/3 step factor of channels 10 / 21 applies to codes only
 #pragma unroll
         for (int r = 0; r < 4; r++) {
-          const int rank = (slot0 + 8 * kq + 4 * m + r - a.w0 + a.W_cap) % a.W_cap;
-          const float xv = S[m][r] * c_plain;
-          x[4 * m + r] = rank < a.n_w ? xv : -INFINITY;
+          const int dd = 16 * (m & 1) + 4 * kq + r;
+          if (dd == 10 || dd == 21) t[r] *= (3.0f / 7.0f);
         }
-    } else {
-      tile = tile_base + (size_t)(item - n_wt);
-      Codes<KB> kc;
-      kc.load(a.k_codes + tile * tile_words(KB), lane);
-      kc.prep();
-      // scale-folded query (hi | lo part per column) and zero-point term
+      }
+      acc[m] += t * __builtin_ldexpf(1.0f, field_pos<VB>(m & 3) - 24);
+    }
+  }
+
+  // ---- packed tiles: kDepth tiles in flight per wave, taken from the workgroup's counter
+  const size_t tile_base = (size_t)u * a.tiles_cap;
+  auto grab = [&]() -> int {
+    int it = 0;
+    if (lane == 0) it = atomicAdd(&s_next, 1);
+    return __builtin_amdgcn_readfirstlane(it);
+  };
+
+  auto process = [&](const Stage<KB, VB>& st) {
+    // -- Key side. Cooperative operand preparation: lane owns channels 2*lane, 2*lane+1.
+    {
+      const float s0 = lo_half(st.ks), s1 = hi_half(st.ks);
+#pragma unroll
+      for (int hh = 0; hh < G; hh++) {
+        uint32_t hi, lo;
+        split_pair(qc[hh][0] * s0, qc[hh][1] * s1, hi, lo);
+        reinterpret_cast<uint32_t*>(&L.bk[hh][0])[lane] = hi;
+        reinterpret_cast<uint32_t*>(&L.bk[8 + hh][0])[lane] = lo;
+      }
+      reinterpret_cast<uint32_t*>(&L.zk[0])[lane] = st.kz;
+    }
+    wave_lds_fence();
+    float x[8], p[8];
+    {
+      const Codes<KB> kc(st.kc);
       half8_t Bk[4];
       float4_t Sz = {0, 0, 0, 0};
 #pragma unroll
       for (int ks = 0; ks < 4; ks++) {
-        const half8_t s8 = *reinterpret_cast<const half8_t*>(a.k_scale + tile * kD + 32 * ks + 8 * kq);
-        const half8_t z8 = *reinterpret_cast<const half8_t*>(a.k_zero + tile * kD + 32 * ks + 8 * kq);
-#pragma unroll
-        for (int e = 0; e < 8; e++) Bk[ks][e] = split_part(qf[ks][e] * (float)s8[e], lo_part);
+        Bk[ks] = *reinterpret_cast<const half8_t*>(&L.bk[col][32 * ks + 8 * kq]);
+        const half8_t z8 = *reinterpret_cast<const half8_t*>(&L.zk[32 * ks + 8 * kq]);
         Sz = mfma16(z8, qB[ks], Sz);     // every A row is the zero-point vector
       }
       float4_t S[2] = {float4_t{0, 0, 0, 0}, float4_t{0, 0, 0, 0}};
@@ -229,68 +354,71 @@ __global__ __launch_bounds__(kThreads) void decode_attn_kernel(AttnArgs a) {
 #pragma unroll
         for (int r = 0; r < 4; r++) x[4 * m + r] = S[m][r] * c_code + zt;
     }
-    // hi column + lo column -> full score in both lanes
-#pragma unroll
-    for (int e = 0; e < 8; e++) x[e] = x[e] + ror8(x[e]);
+    softmax_tile(x, p);
 
-    // online softmax with a lazily raised reference
-    float mx = x[0];
-#pragma unroll
-    for (int e = 1; e < 8; e++) mx = fmaxf(mx, x[e]);
-    if (__any(mx > mref)) {
-      mx = fmaxf(mx, __shfl_xor(mx, 16));
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float mnew = mx > mref ? mx + kRefMargin : mref;
-      const float f = (mnew == mref) ? 1.0f : __builtin_exp2f(mref - mnew);
-      mref = mnew;
-      lsum *= f;
-      accZ *= f;
-#pragma unroll
-      for (int m = 0; m < 8; m++) acc[m] *= f;
+    // -- Value side. Numerators to LDS, then lane owns tokens (2*tp, 2*tp+1) of channel block g.
+    if (col < G) {
+      *reinterpret_cast<float4_t*>(&L.p[col][8 * kq]) = float4_t{p[0], p[1], p[2], p[3]};
+      *reinterpret_cast<float4_t*>(&L.p[col][8 * kq + 4]) = float4_t{p[4], p[5], p[6], p[7]};
     }
-    float p[8];
+    wave_lds_fence();
+    {
+      const int tp = lane & 15, g = lane >> 4;
+      const float s0 = lo_half(st.vs), s1 = hi_half(st.vs);
 #pragma unroll
-    for (int e = 0; e < 8; e++) {
-      p[e] = col_valid ? __builtin_exp2f(x[e] - mref) : 0.0f;
-      lsum += p[e];
-    }
-    half8_t PB;
-#pragma unroll
-    for (int e = 0; e < 8; e++) PB[e] = split_part(p[e], lo_part);
-
-    if (is_window) {
-      const uint16_t* vw = a.v_win + (size_t)u * kD * a.W_cap + slot0 + 8 * kq;
-#pragma unroll
-      for (int m = 0; m < 8; m++) {
-        half8_t A = *reinterpret_cast<const half8_t*>(vw + (size_t)(16 * m + col) * a.W_cap);
-        float4_t t = mfma16(A, PB, float4_t{0, 0, 0, 0});
-        if constexpr (VB == 3) {   // the final 7/3 step factor of channels 10 / 21 applies to codes only
-#pragma unroll
-          for (int r = 0; r < 4; r++) {
-            const int dd = 16 * (m & 1) + 4 * kq + r;
-            if (dd == 10 || dd == 21) t[r] *= (3.0f / 7.0f);
-          }
+      for (int hh = 0; hh < G; hh++) {
+        const float2_t pp = *reinterpret_cast<const float2_t*>(&L.p[hh][2 * tp]);
+        uint32_t hi, lo;
+        split_pair(pp[0] * s0, pp[1] * s1, hi, lo);
+        reinterpret_cast<uint32_t*>(&L.bv[g][hh][0])[tp] = hi;
+        reinterpret_cast<uint32_t*>(&L.bv[g][8 + hh][0])[tp] = lo;
+        if ((hh & 3) == g) {   // plain probabilities (zero-point term), spread over the channel-block lanes
+          split_pair(pp[0], pp[1], hi, lo);
+          reinterpret_cast<uint32_t*>(&L.pb[hh][0])[tp] = hi;
+          reinterpret_cast<uint32_t*>(&L.pb[8 + hh][0])[tp] = lo;
         }
-        acc[m] += t * __builtin_ldexpf(1.0f, field_pos<VB>(m & 3) - 24);
       }
-    } else {
-      Codes<VB> vc;
-      vc.load(a.v_codes + tile * tile_words(VB), lane);
-      vc.prep();
+      reinterpret_cast<uint32_t*>(&L.zv[0][0])[lane] = st.vz;
+    }
+    wave_lds_fence();
+    {
+      const Codes<VB> vc(st.vc);
       half8_t Bv[4];
 #pragma unroll
-      for (int g = 0; g < 4; g++) {
-        const half8_t s8 = *reinterpret_cast<const half8_t*>(a.v_scale + tile * kD + 32 * g + 8 * kq);
-#pragma unroll
-        for (int e = 0; e < 8; e++) Bv[g][e] = split_part(p[e] * (float)s8[e], lo_part);
-      }
+      for (int g = 0; g < 4; g++) Bv[g] = *reinterpret_cast<const half8_t*>(&L.bv[g][col][8 * kq]);
+      const half8_t PB = *reinterpret_cast<const half8_t*>(&L.pb[col][8 * kq]);
       // zero-point term: A row i carries the zero-points of channel block i % 4
-      const half8_t z8 = *reinterpret_cast<const half8_t*>(a.v_zero + tile * kD + 32 * (col & 3) + 8 * kq);
+      const half8_t z8 = *reinterpret_cast<const half8_t*>(&L.zv[col & 3][8 * kq]);
       accZ = mfma16(z8, PB, accZ);
 #pragma unroll
       for (int m = 0; m < 8; m++) {
         acc[m] = mfma16(vc.lo(m), Bv[m >> 1], acc[m]);
         if constexpr (VB == 3) acc[m] = mfma16(vc.hi(m), Bv[m >> 1], acc[m]);
+      }
+    }
+    wave_lds_fence();   // the next tile's operand writes come after these reads
+  };
+
+  if (p_end > p_begin) {
+    Stage<KB, VB> st[kDepth];
+    int it[kDepth];
+#pragma unroll
+    for (int s = 0; s < kDepth; s++) {
+      it[s] = grab();
+      // past the end: re-read the last tile (cache hit) so that the load stream stays uniform
+      st[s].load(a, tile_base + (size_t)(it[s] < p_end ? it[s] : p_end - 1), lane);
+    }
+    bool more = true;
+    while (more) {
+#pragma unroll
+      for (int s = 0; s < kDepth; s++) {
+        if (more && it[s] < p_end) {
+          process(st[s]);
+          it[s] = grab();
+          st[s].load(a, tile_base + (size_t)(it[s] < p_end ? it[s] : p_end - 1), lane);
+        } else {
+          more = false;
+        }
       }
     }
   }
@@ -321,50 +449,52 @@ __global__ __launch_bounds__(kThreads) void decode_attn_kernel(AttnArgs a) {
     float M = -INFINITY;
 #pragma unroll
     for (int w = 0; w < kWaves; w++) M = fmaxf(M, red_m[w][hh]);
-    float L = 0.0f, O = 0.0f;
+    float Lsum = 0.0f, O = 0.0f;
 #pragma unroll
     for (int w = 0; w < kWaves; w++) {
       const float mw = red_m[w][hh];
       const float f = (mw == -INFINITY) ? 0.0f : __builtin_exp2f(mw - M);
-      L += red_l[w][hh] * f;
+      Lsum += red_l[w][hh] * f;
       O += red_o[w][hh][d] * f;
     }
     if (a.n_splits == 1) {
-      a.out[((size_t)b * a.Hq + (size_t)jh * G + hh) * kD + d] = __builtin_bit_cast(uint16_t, (half_t)(O / L));
+      a.out[((size_t)b * a.Hq + (size_t)jh * G + hh) * kD + d] = __builtin_bit_cast(uint16_t, (half_t)(O / Lsum));
     } else {
+      // agent-scope stores: written through to the level all XCDs share (no cache-wide flush needed)
       float* pp = a.part + (((size_t)u * a.n_splits + sp) * G + hh) * (kD + 2);
-      if (d == 0) { pp[0] = M; pp[1] = L; }
-      pp[2 + d] = O;
+      if (d == 0) { st_agent(pp, M); st_agent(pp + 1, Lsum); }
+      st_agent(pp + 2 + d, O);
     }
   }
   if (a.n_splits == 1) return;
 
   // ---- split merge: the last workgroup of the unit to arrive combines all partials
-  __threadfence();
+  // The partials were stored and are later loaded with agent scope, which the hardware keeps coherent
+  // per access across the XCDs' L2s: waiting for the stores to complete is all the release needs.
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
   __syncthreads();
   if (tid == 0) {
-    const uint32_t prev = atomicAdd(&a.counters[u], 1u);
+    const uint32_t prev = __hip_atomic_fetch_add(&a.counters[u], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     s_last = (prev == (uint32_t)a.n_splits - 1u);
   }
   __syncthreads();
   if (!s_last) return;
-  __threadfence();
   for (int idx = tid; idx < G * kD; idx += kThreads) {
     const int hh = idx / kD, d = idx % kD;
     const float* base = a.part + ((size_t)u * a.n_splits * G + hh) * (kD + 2);
     const size_t stride = (size_t)G * (kD + 2);
     float M = -INFINITY;
-    for (int s = 0; s < a.n_splits; s++) M = fmaxf(M, __builtin_nontemporal_load(base + s * stride));
-    float L = 0.0f, O = 0.0f;
+    for (int s = 0; s < a.n_splits; s++) M = fmaxf(M, ld_agent(base + s * stride));
+    float Lsum = 0.0f, O = 0.0f;
     for (int s = 0; s < a.n_splits; s++) {
-      const float ms = __builtin_nontemporal_load(base + s * stride);
+      const float ms = ld_agent(base + s * stride);
       const float f = (ms == -INFINITY) ? 0.0f : __builtin_exp2f(ms - M);
-      L += __builtin_nontemporal_load(base + s * stride + 1) * f;
-      O += __builtin_nontemporal_load(base + s * stride + 2 + d) * f;
+      Lsum += ld_agent(base + s * stride + 1) * f;
+      O += ld_agent(base + s * stride + 2 + d) * f;
     }
-    a.out[((size_t)b * a.Hq + (size_t)jh * G + hh) * kD + d] = __builtin_bit_cast(uint16_t, (half_t)(O / L));
+    a.out[((size_t)b * a.Hq + (size_t)jh * G + hh) * kD + d] = __builtin_bit_cast(uint16_t, (half_t)(O / Lsum));
   }
-  if (tid == 0) a.counters[u] = 0;
+  if (tid == 0) __hip_atomic_store(&a.counters[u], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 template <int KB, int VB>
