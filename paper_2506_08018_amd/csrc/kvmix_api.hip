@@ -9,6 +9,7 @@ using namespace kvmix;
 namespace {
 
 std::atomic<int> g_last_hip_error{0};
+constexpr int kNumCUs = 256;   // MI355X
 
 int hip_fail(hipError_t e) {
   g_last_hip_error.store((int)e);
@@ -188,8 +189,8 @@ int kvmix_decode_attn(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const u
   const int n_items = c->W_cap / kTile + c->n_q / kTile;
   if (n_splits < 0 || n_splits > max_splits(sh)) return KVMIX_ERR_BAD_SHAPE;
   if (n_splits == 0) {
-    // enough workgroups to give every CU two, each with at least 8 tiles of work
-    n_splits = (512 + units - 1) / units;
+    // one workgroup occupies a whole CU (LDS): aim at one workgroup per CU, at least 8 tiles each
+    n_splits = kNumCUs / units;
     if (n_splits > n_items / 8) n_splits = n_items / 8;
     if (n_splits > max_splits(sh)) n_splits = max_splits(sh);
     if (n_splits < 1) n_splits = 1;

@@ -26,12 +26,15 @@ namespace kvmix {
 
 namespace {
 
-constexpr int kWaves = 8;
+constexpr int kWaves = 12;           // 3 waves per SIMD: the register budget is 512 / 3 per lane
 constexpr int kThreads = kWaves * kWave;
 constexpr int kDepth = 3;            // tiles in flight per wave
 constexpr float kRefMargin = 4.0f;   // reference maximum is raised to (tile max + margin), log2 units
 
 typedef float float2_t __attribute__((ext_vector_type(2)));
+
+// 2^x by the hardware instruction alone (results below 2^-126 flush to zero, which is harmless here)
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 __device__ __forceinline__ float4_t mfma16(half8_t a, half8_t b, float4_t c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
@@ -156,25 +159,34 @@ __device__ __forceinline__ half_t split_part(float x, bool lo_part) {
 __device__ __forceinline__ float lo_half(uint32_t v) { return (float)__builtin_bit_cast(half_t, (uint16_t)(v & 0xffffu)); }
 __device__ __forceinline__ float hi_half(uint32_t v) { return (float)__builtin_bit_cast(half_t, (uint16_t)(v >> 16)); }
 
-// Wave-private LDS exchange area (row pitches chosen so that the 16 columns of a 16-byte
-// operand read fall into distinct banks).
-struct __attribute__((aligned(16))) WaveLds {
-  uint16_t bk[16][kD + 8];   // scale-folded query, column-major: [column][channel], pitch 272 B
-  uint16_t zk[kD];           // Key zero-points of the tile
-  float p[8][kTile];         // softmax numerators [head][token]
-  uint16_t bv[4][16][kTile + 8];  // scale-folded probabilities [channel block][column][token], pitch 80 B
-  uint16_t pb[16][kTile + 8];     // probabilities split hi/lo [column][token]
-  uint16_t zv[4][kTile];     // Value zero-points [channel block][token]
+// Wave-private LDS exchange area. Operand rows exist for the 2*G used MFMA columns only (hi parts in
+// rows 0..G-1, lo parts in rows G..2G-1); the lanes of unused columns all read the extra zero row.
+// Row pitches (272 B, 80 B) put the rows read by one 16-byte operand load into distinct banks.
+template <int G> struct __attribute__((aligned(16))) WaveLds {
+  static constexpr int kRows = 2 * G;      // index of the zero row
+  uint16_t bk[kRows + 1][kD + 8];          // scale-folded query [row][channel]
+  uint16_t zk[kD];                         // Key zero-points of the tile
+  float p[G][kTile];                       // softmax numerators [head][token]
+  uint16_t bv[4][kRows + 1][kTile + 8];    // scale-folded probabilities [channel block][row][token]
+  uint16_t pb[kRows + 1][kTile + 8];       // probabilities split hi/lo [row][token]
+  uint16_t zv[4][kTile];                   // Value zero-points [channel block][token]
 };
+
+template <int G> struct MergeLds {        // per-wave results, reuses the exchange memory after the main loop
+  float o[kWaves][G][kD];
+  float m[kWaves][G];
+  float l[kWaves][G];
+};
+
+template <int G> constexpr size_t smem_bytes() {
+  return sizeof(WaveLds<G>) * kWaves > sizeof(MergeLds<G>) ? sizeof(WaveLds<G>) * kWaves : sizeof(MergeLds<G>);
+}
 
 template <int KB, int VB, int G>
 __global__ __launch_bounds__(kThreads) void decode_attn_kernel(AttnArgs a) {
-  __shared__ WaveLds lds_all[kWaves];
+  __shared__ __attribute__((aligned(16))) char smem[smem_bytes<G>()];
   __shared__ int s_next;
   __shared__ int s_last;
-  __shared__ float red_o[kWaves][G][kD];
-  __shared__ float red_m[kWaves][G];
-  __shared__ float red_l[kWaves][G];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int col = lane & 15, kq = lane >> 4;         // MFMA column / row index, k-quarter
@@ -183,7 +195,9 @@ __global__ __launch_bounds__(kThreads) void decode_attn_kernel(AttnArgs a) {
   const bool col_valid = h < G;
   const int sp = blockIdx.x, u = blockIdx.y;
   const int b = u / a.Hkv, jh = u % a.Hkv;
-  WaveLds& L = lds_all[wave];
+  WaveLds<G>& L = reinterpret_cast<WaveLds<G>*>(smem)[wave];
+  MergeLds<G>& R = *reinterpret_cast<MergeLds<G>*>(smem);
+  const int row = col_valid ? (lo_part ? G + h : h) : WaveLds<G>::kRows;   // operand row of this lane's column
 
   // work items of this split: window tiles first, then packed tiles
   const int n_wt = a.W_cap / kTile;
@@ -199,7 +213,7 @@ __global__ __launch_bounds__(kThreads) void decode_attn_kernel(AttnArgs a) {
   // zero the exchange area: rows of unused columns stay zero for the whole kernel
   {
     u32x4_t* z = reinterpret_cast<u32x4_t*>(&L);
-    for (int i = lane; i < (int)(sizeof(WaveLds) / 16); i += kWave) z[i] = u32x4_t{0, 0, 0, 0};
+    for (int i = lane; i < (int)(sizeof(WaveLds<G>) / 16); i += kWave) z[i] = u32x4_t{0, 0, 0, 0};
   }
   __syncthreads();
 
@@ -224,6 +238,8 @@ __global__ __launch_bounds__(kThreads) void decode_attn_kernel(AttnArgs a) {
     }
   }
 
+  const half8_t zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+  const half8_t ones8 = {1, 1, 1, 1, 1, 1, 1, 1};
   const float c_code = a.scale_log2 * 16777216.0f;   // code products carry 2^-24
   const float c_plain = a.scale_log2;
 
@@ -231,32 +247,32 @@ __global__ __launch_bounds__(kThreads) void decode_attn_kernel(AttnArgs a) {
   float4_t accZ = {0, 0, 0, 0};
 #pragma unroll
   for (int m = 0; m < 8; m++) acc[m] = float4_t{0, 0, 0, 0};
-  float mref = -INFINITY, lsum = 0.0f;
+  float mref = -INFINITY;
 
-  // online softmax of the lane's 8 scores (tokens 8*kq + e of the tile, column col): raises the
-  // reference if needed (rescaling the accumulators) and returns the numerators
-  auto softmax_tile = [&](float (&x)[8], float (&p)[8]) {
+  // online softmax of the lane's 8 tokens (8*kq + e of the tile, column col). The score of token e is
+  // s[e]*c + z (log2 domain) summed over the hi and lo columns; z is zero in lo columns. Raises the
+  // reference if needed (rescaling the accumulators) and returns the numerators 2^(score - reference).
+  auto softmax_tile = [&](float (&s)[8], float c, float z, float (&p)[8]) {
 #pragma unroll
-    for (int e = 0; e < 8; e++) x[e] = x[e] + ror8(x[e]);   // hi column + lo column
-    float mx = x[0];
-#pragma unroll
-    for (int e = 1; e < 8; e++) mx = fmaxf(mx, x[e]);
+    for (int e = 0; e < 8; e++) s[e] = s[e] + ror8(s[e]);   // hi column + lo column
+    z = z + ror8(z);
+    float mx = fmaxf(fmaxf(s[0], s[1]), s[2]);
+    mx = fmaxf(fmaxf(mx, s[3]), s[4]);
+    mx = fmaxf(fmaxf(mx, s[5]), s[6]);
+    mx = fmaxf(mx, s[7]) * c + z;                           // c > 0
     if (__any(mx > mref)) {
       mx = fmaxf(mx, __shfl_xor(mx, 16));
       mx = fmaxf(mx, __shfl_xor(mx, 32));
       const float mnew = mx > mref ? mx + kRefMargin : mref;
-      const float f = (mnew == mref) ? 1.0f : __builtin_exp2f(mref - mnew);
+      const float f = (mnew == mref) ? 1.0f : fast_exp2(mref - mnew);
       mref = mnew;
-      lsum *= f;
       accZ *= f;
 #pragma unroll
       for (int m = 0; m < 8; m++) acc[m] *= f;
     }
+    const float off = z - mref;
 #pragma unroll
-    for (int e = 0; e < 8; e++) {
-      p[e] = col_valid ? __builtin_exp2f(x[e] - mref) : 0.0f;
-      lsum += p[e];
-    }
+    for (int e = 0; e < 8; e++) p[e] = fast_exp2(s[e] * c + off);
   };
 
   // ---- fp16 window tiles (few): taken round-robin by the waves before the packed stream
@@ -284,11 +300,12 @@ __global__ __launch_bounds__(kThreads) void decode_attn_kernel(AttnArgs a) {
 #pragma unroll
     for (int m = 0; m < 2; m++)
 #pragma unroll
-      for (int r = 0; r < 4; r++) x[4 * m + r] = (first + 8 * kq + 4 * m + r) < a.n_w ? S[m][r] * c_plain : -INFINITY;
-    softmax_tile(x, p);
+      for (int r = 0; r < 4; r++) x[4 * m + r] = (first + 8 * kq + 4 * m + r) < a.n_w ? S[m][r] : -INFINITY;
+    softmax_tile(x, c_plain, 0.0f, p);
     half8_t PB;
 #pragma unroll
-    for (int e = 0; e < 8; e++) PB[e] = split_part(p[e], lo_part);
+    for (int e = 0; e < 8; e++) PB[e] = split_part(col_valid ? p[e] : 0.0f, lo_part);
+    accZ = mfma16(col >= 4 ? ones8 : zero8, PB, accZ);   // rows 4..15 accumulate the sum of numerators
 #pragma unroll
     for (int m = 0; m < 8; m++) {
       float4_t t = mfma16(Av[m], PB, float4_t{0, 0, 0, 0});
@@ -320,19 +337,19 @@ __global__ __launch_bounds__(kThreads) void decode_attn_kernel(AttnArgs a) {
         uint32_t hi, lo;
         split_pair(qc[hh][0] * s0, qc[hh][1] * s1, hi, lo);
         reinterpret_cast<uint32_t*>(&L.bk[hh][0])[lane] = hi;
-        reinterpret_cast<uint32_t*>(&L.bk[8 + hh][0])[lane] = lo;
+        reinterpret_cast<uint32_t*>(&L.bk[G + hh][0])[lane] = lo;
       }
       reinterpret_cast<uint32_t*>(&L.zk[0])[lane] = st.kz;
     }
     wave_lds_fence();
-    float x[8], p[8];
+    float x[8], p[8], zt;
     {
       const Codes<KB> kc(st.kc);
       half8_t Bk[4];
       float4_t Sz = {0, 0, 0, 0};
 #pragma unroll
       for (int ks = 0; ks < 4; ks++) {
-        Bk[ks] = *reinterpret_cast<const half8_t*>(&L.bk[col][32 * ks + 8 * kq]);
+        Bk[ks] = *reinterpret_cast<const half8_t*>(&L.bk[row][32 * ks + 8 * kq]);
         const half8_t z8 = *reinterpret_cast<const half8_t*>(&L.zk[32 * ks + 8 * kq]);
         Sz = mfma16(z8, qB[ks], Sz);     // every A row is the zero-point vector
       }
@@ -348,13 +365,13 @@ __global__ __launch_bounds__(kThreads) void decode_attn_kernel(AttnArgs a) {
         if (kq == 1) S[0][2] *= (7.0f / 3.0f);
         if (kq == 2) S[1][1] *= (7.0f / 3.0f);
       }
-      const float zt = Sz[0] * c_plain;
+      zt = Sz[0] * c_plain;
 #pragma unroll
       for (int m = 0; m < 2; m++)
 #pragma unroll
-        for (int r = 0; r < 4; r++) x[4 * m + r] = S[m][r] * c_code + zt;
+        for (int r = 0; r < 4; r++) x[4 * m + r] = S[m][r];
     }
-    softmax_tile(x, p);
+    softmax_tile(x, c_code, zt, p);
 
     // -- Value side. Numerators to LDS, then lane owns tokens (2*tp, 2*tp+1) of channel block g.
     if (col < G) {
@@ -371,11 +388,11 @@ __global__ __launch_bounds__(kThreads) void decode_attn_kernel(AttnArgs a) {
         uint32_t hi, lo;
         split_pair(pp[0] * s0, pp[1] * s1, hi, lo);
         reinterpret_cast<uint32_t*>(&L.bv[g][hh][0])[tp] = hi;
-        reinterpret_cast<uint32_t*>(&L.bv[g][8 + hh][0])[tp] = lo;
+        reinterpret_cast<uint32_t*>(&L.bv[g][G + hh][0])[tp] = lo;
         if ((hh & 3) == g) {   // plain probabilities (zero-point term), spread over the channel-block lanes
           split_pair(pp[0], pp[1], hi, lo);
           reinterpret_cast<uint32_t*>(&L.pb[hh][0])[tp] = hi;
-          reinterpret_cast<uint32_t*>(&L.pb[8 + hh][0])[tp] = lo;
+          reinterpret_cast<uint32_t*>(&L.pb[G + hh][0])[tp] = lo;
         }
       }
       reinterpret_cast<uint32_t*>(&L.zv[0][0])[lane] = st.vz;
@@ -385,10 +402,12 @@ __global__ __launch_bounds__(kThreads) void decode_attn_kernel(AttnArgs a) {
       const Codes<VB> vc(st.vc);
       half8_t Bv[4];
 #pragma unroll
-      for (int g = 0; g < 4; g++) Bv[g] = *reinterpret_cast<const half8_t*>(&L.bv[g][col][8 * kq]);
-      const half8_t PB = *reinterpret_cast<const half8_t*>(&L.pb[col][8 * kq]);
-      // zero-point term: A row i carries the zero-points of channel block i % 4
-      const half8_t z8 = *reinterpret_cast<const half8_t*>(&L.zv[col & 3][8 * kq]);
+      for (int g = 0; g < 4; g++) Bv[g] = *reinterpret_cast<const half8_t*>(&L.bv[g][row][8 * kq]);
+      const half8_t PB = *reinterpret_cast<const half8_t*>(&L.pb[row][8 * kq]);
+      // zero-point term: A rows 0..3 carry the zero-points of channel blocks 0..3, rows 4..15 are ones
+      // and accumulate the sum of the numerators
+      half8_t z8 = ones8;
+      if (col < 4) z8 = *reinterpret_cast<const half8_t*>(&L.zv[col][8 * kq]);
       accZ = mfma16(z8, PB, accZ);
 #pragma unroll
       for (int m = 0; m < 8; m++) {
@@ -423,9 +442,15 @@ __global__ __launch_bounds__(kThreads) void decode_attn_kernel(AttnArgs a) {
     }
   }
 
-  // ---- per-wave result: undo the field scaling, add hi and lo columns, add the zero-point term
-  lsum += __shfl_xor(lsum, 16);
-  lsum += __shfl_xor(lsum, 32);
+  // ---- per-wave result: undo the field scaling, add hi and lo columns, add the zero-point term.
+  // accZ: lanes with kq == 0 hold the zero-point sums of channel blocks 0..3, lanes with kq >= 1 the
+  // sum of numerators (any register).
+  __syncthreads();   // every wave is done with its exchange area: the memory now holds the per-wave results
+  float zsum[4];
+#pragma unroll
+  for (int g = 0; g < 4; g++) zsum[g] = __shfl(accZ[g], col);
+  float lsum = __shfl(accZ[0], 16 + col);
+  lsum += ror8(lsum);
 #pragma unroll
   for (int m = 0; m < 8; m++) {
     const float sc = __builtin_ldexpf(1.0f, 24 - field_pos<VB>(m & 3));
@@ -436,26 +461,26 @@ __global__ __launch_bounds__(kThreads) void decode_attn_kernel(AttnArgs a) {
         const int dd = 16 * (m & 1) + 4 * kq + r;
         if (dd == 10 || dd == 21) v *= (7.0f / 3.0f);
       }
-      v += accZ[(m >> 1)];          // row 4*kq' + r of accZ is channel block r: pick block m/2
+      v += zsum[m >> 1];
       v += ror8(v);
-      if (col < G) red_o[wave][col][16 * m + 4 * kq + r] = v;
+      if (col < G) R.o[wave][col][16 * m + 4 * kq + r] = v;
     }
   }
-  if (col < G && kq == 0) { red_m[wave][col] = mref; red_l[wave][col] = lsum; }
+  if (col < G && kq == 0) { R.m[wave][col] = mref; R.l[wave][col] = lsum; }
   __syncthreads();
 
   for (int idx = tid; idx < G * kD; idx += kThreads) {
     const int hh = idx / kD, d = idx % kD;
     float M = -INFINITY;
 #pragma unroll
-    for (int w = 0; w < kWaves; w++) M = fmaxf(M, red_m[w][hh]);
+    for (int w = 0; w < kWaves; w++) M = fmaxf(M, R.m[w][hh]);
     float Lsum = 0.0f, O = 0.0f;
 #pragma unroll
     for (int w = 0; w < kWaves; w++) {
-      const float mw = red_m[w][hh];
-      const float f = (mw == -INFINITY) ? 0.0f : __builtin_exp2f(mw - M);
-      Lsum += red_l[w][hh] * f;
-      O += red_o[w][hh][d] * f;
+      const float mw = R.m[w][hh];
+      const float f = (mw == -INFINITY) ? 0.0f : fast_exp2(mw - M);
+      Lsum += R.l[w][hh] * f;
+      O += R.o[w][hh][d] * f;
     }
     if (a.n_splits == 1) {
       a.out[((size_t)b * a.Hq + (size_t)jh * G + hh) * kD + d] = __builtin_bit_cast(uint16_t, (half_t)(O / Lsum));
@@ -488,7 +513,7 @@ __global__ __launch_bounds__(kThreads) void decode_attn_kernel(AttnArgs a) {
     float Lsum = 0.0f, O = 0.0f;
     for (int s = 0; s < a.n_splits; s++) {
       const float ms = ld_agent(base + s * stride);
-      const float f = (ms == -INFINITY) ? 0.0f : __builtin_exp2f(ms - M);
+      const float f = (ms == -INFINITY) ? 0.0f : fast_exp2(ms - M);
       Lsum += ld_agent(base + s * stride + 1) * f;
       O += ld_agent(base + s * stride + 2 + d) * f;
     }
