@@ -26,8 +26,8 @@ namespace kvmix {
 
 namespace {
 
-constexpr int kWaves = 12;           // 3 waves per SIMD: the register budget is 512 / 3 per lane
-constexpr int kThreads = kWaves * kWave;
+// waves per workgroup: 3 per SIMD where the LDS exchange areas fit (register budget 512 / 3 per lane)
+constexpr int waves_for(int G) { return G == 8 ? 8 : 12; }
 constexpr int kDepth = 3;            // tiles in flight per wave
 constexpr float kRefMargin = 4.0f;   // reference maximum is raised to (tile max + margin), log2 units
 
@@ -166,24 +166,26 @@ template <int G> struct __attribute__((aligned(16))) WaveLds {
   static constexpr int kRows = 2 * G;      // index of the zero row
   uint16_t bk[kRows + 1][kD + 8];          // scale-folded query [row][channel]
   uint16_t zk[kD];                         // Key zero-points of the tile
-  float p[G][kTile];                       // softmax numerators [head][token]
+  float s[2 * G][kTile];                   // raw code sums of the tile [row][token] (hi rows, then lo rows)
   uint16_t bv[4][kRows + 1][kTile + 8];    // scale-folded probabilities [channel block][row][token]
   uint16_t pb[kRows + 1][kTile + 8];       // probabilities split hi/lo [row][token]
   uint16_t zv[4][kTile];                   // Value zero-points [channel block][token]
 };
 
 template <int G> struct MergeLds {        // per-wave results, reuses the exchange memory after the main loop
-  float o[kWaves][G][kD];
-  float m[kWaves][G];
-  float l[kWaves][G];
+  float o[waves_for(G)][G][kD];
+  float m[waves_for(G)][G];
+  float l[waves_for(G)][G];
 };
 
 template <int G> constexpr size_t smem_bytes() {
-  return sizeof(WaveLds<G>) * kWaves > sizeof(MergeLds<G>) ? sizeof(WaveLds<G>) * kWaves : sizeof(MergeLds<G>);
+  return sizeof(WaveLds<G>) * waves_for(G) > sizeof(MergeLds<G>) ? sizeof(WaveLds<G>) * waves_for(G) : sizeof(MergeLds<G>);
 }
 
 template <int KB, int VB, int G>
-__global__ __launch_bounds__(kThreads) void decode_attn_kernel(AttnArgs a) {
+__global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnArgs a) {
+  constexpr int kWaves = waves_for(G);
+  constexpr int kThreads = kWaves * kWave;
   __shared__ __attribute__((aligned(16))) char smem[smem_bytes<G>()];
   __shared__ int s_next;
   __shared__ int s_last;
@@ -252,14 +254,9 @@ __global__ __launch_bounds__(kThreads) void decode_attn_kernel(AttnArgs a) {
   // online softmax of the lane's 8 tokens (8*kq + e of the tile, column col). The score of token e is
   // s[e]*c + z (log2 domain) summed over the hi and lo columns; z is zero in lo columns. Raises the
   // reference if needed (rescaling the accumulators) and returns the numerators 2^(score - reference).
-  auto softmax_tile = [&](float (&s)[8], float c, float z, float (&p)[8]) {
-#pragma unroll
-    for (int e = 0; e < 8; e++) s[e] = s[e] + ror8(s[e]);   // hi column + lo column
-    z = z + ror8(z);
-    float mx = fmaxf(fmaxf(s[0], s[1]), s[2]);
-    mx = fmaxf(fmaxf(mx, s[3]), s[4]);
-    mx = fmaxf(fmaxf(mx, s[5]), s[6]);
-    mx = fmaxf(mx, s[7]) * c + z;                           // c > 0
+  // raises the per-column reference to cover mx (log2-domain upper estimate of the tile's scores,
+  // identical in all lanes of a column pair) and rescales the accumulators accordingly
+  auto raise_reference = [&](float mx) {
     if (__any(mx > mref)) {
       mx = fmaxf(mx, __shfl_xor(mx, 16));
       mx = fmaxf(mx, __shfl_xor(mx, 32));
@@ -270,9 +267,12 @@ __global__ __launch_bounds__(kThreads) void decode_attn_kernel(AttnArgs a) {
 #pragma unroll
       for (int m = 0; m < 8; m++) acc[m] *= f;
     }
-    const float off = z - mref;
-#pragma unroll
-    for (int e = 0; e < 8; e++) p[e] = fast_exp2(s[e] * c + off);
+  };
+  auto max8 = [](const float (&s)[8]) {
+    float mx = fmaxf(fmaxf(s[0], s[1]), s[2]);
+    mx = fmaxf(fmaxf(mx, s[3]), s[4]);
+    mx = fmaxf(fmaxf(mx, s[5]), s[6]);
+    return fmaxf(mx, s[7]);
   };
 
   // ---- fp16 window tiles (few): taken round-robin by the waves before the packed stream
@@ -301,7 +301,11 @@ __global__ __launch_bounds__(kThreads) void decode_attn_kernel(AttnArgs a) {
     for (int m = 0; m < 2; m++)
 #pragma unroll
       for (int r = 0; r < 4; r++) x[4 * m + r] = (first + 8 * kq + 4 * m + r) < a.n_w ? S[m][r] : -INFINITY;
-    softmax_tile(x, c_plain, 0.0f, p);
+#pragma unroll
+    for (int e = 0; e < 8; e++) x[e] = x[e] + ror8(x[e]);   // hi column + lo column (lo is zero here)
+    raise_reference(max8(x) * c_plain);
+#pragma unroll
+    for (int e = 0; e < 8; e++) p[e] = fast_exp2(x[e] * c_plain - mref);
     half8_t PB;
 #pragma unroll
     for (int e = 0; e < 8; e++) PB[e] = split_part(col_valid ? p[e] : 0.0f, lo_part);
@@ -328,7 +332,7 @@ __global__ __launch_bounds__(kThreads) void decode_attn_kernel(AttnArgs a) {
     return __builtin_amdgcn_readfirstlane(it);
   };
 
-  auto process = [&](const Stage<KB, VB>& st) {
+  auto process = [&](const Stage<KB, VB>& st, bool live) {
     // -- Key side. Cooperative operand preparation: lane owns channels 2*lane, 2*lane+1.
     {
       const float s0 = lo_half(st.ks), s1 = hi_half(st.ks);
@@ -342,7 +346,7 @@ __global__ __launch_bounds__(kThreads) void decode_attn_kernel(AttnArgs a) {
       reinterpret_cast<uint32_t*>(&L.zk[0])[lane] = st.kz;
     }
     wave_lds_fence();
-    float x[8], p[8], zt;
+    float x[8], zt;
     {
       const Codes<KB> kc(st.kc);
       half8_t Bk[4];
@@ -371,12 +375,18 @@ __global__ __launch_bounds__(kThreads) void decode_attn_kernel(AttnArgs a) {
 #pragma unroll
         for (int r = 0; r < 4; r++) x[4 * m + r] = S[m][r];
     }
-    softmax_tile(x, c_code, zt, p);
+    // Reference maximum from the hi column (the lo column changes a score by < 2^-10 of its size, which a
+    // reference does not need); lo lanes take their partner's value so that a column pair stays in step.
+    float mx = max8(x) * c_code + zt;
+    mx = lo_part ? ror8(mx) : mx;
+    raise_reference(live ? mx : -INFINITY);
+    const float off_col = zt - mref;          // meaningful in hi lanes: score = sum * c_code + off_col + reference
 
-    // -- Value side. Numerators to LDS, then lane owns tokens (2*tp, 2*tp+1) of channel block g.
-    if (col < G) {
-      *reinterpret_cast<float4_t*>(&L.p[col][8 * kq]) = float4_t{p[0], p[1], p[2], p[3]};
-      *reinterpret_cast<float4_t*>(&L.p[col][8 * kq + 4]) = float4_t{p[4], p[5], p[6], p[7]};
+    // -- Value side. Raw sums to LDS; lane (tp, g) then owns tokens (2*tp, 2*tp+1) of channel block g:
+    // it finishes the softmax numerators of its two tokens and folds the Value scales into them.
+    if (col_valid) {
+      *reinterpret_cast<float4_t*>(&L.s[row][8 * kq]) = float4_t{x[0], x[1], x[2], x[3]};
+      *reinterpret_cast<float4_t*>(&L.s[row][8 * kq + 4]) = float4_t{x[4], x[5], x[6], x[7]};
     }
     wave_lds_fence();
     {
@@ -384,13 +394,18 @@ __global__ __launch_bounds__(kThreads) void decode_attn_kernel(AttnArgs a) {
       const float s0 = lo_half(st.vs), s1 = hi_half(st.vs);
 #pragma unroll
       for (int hh = 0; hh < G; hh++) {
-        const float2_t pp = *reinterpret_cast<const float2_t*>(&L.p[hh][2 * tp]);
+        float off = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, off_col), hh));
+        off = live ? off : -INFINITY;          // a dead tile (past the end) contributes nothing
+        const float2_t sh = *reinterpret_cast<const float2_t*>(&L.s[hh][2 * tp]);
+        const float2_t sl = *reinterpret_cast<const float2_t*>(&L.s[G + hh][2 * tp]);
+        const float p0 = fast_exp2((sh[0] + sl[0]) * c_code + off);
+        const float p1 = fast_exp2((sh[1] + sl[1]) * c_code + off);
         uint32_t hi, lo;
-        split_pair(pp[0] * s0, pp[1] * s1, hi, lo);
+        split_pair(p0 * s0, p1 * s1, hi, lo);
         reinterpret_cast<uint32_t*>(&L.bv[g][hh][0])[tp] = hi;
         reinterpret_cast<uint32_t*>(&L.bv[g][G + hh][0])[tp] = lo;
         if ((hh & 3) == g) {   // plain probabilities (zero-point term), spread over the channel-block lanes
-          split_pair(pp[0], pp[1], hi, lo);
+          split_pair(p0, p1, hi, lo);
           reinterpret_cast<uint32_t*>(&L.pb[hh][0])[tp] = hi;
           reinterpret_cast<uint32_t*>(&L.pb[G + hh][0])[tp] = lo;
         }
@@ -421,23 +436,20 @@ __global__ __launch_bounds__(kThreads) void decode_attn_kernel(AttnArgs a) {
   if (p_end > p_begin) {
     Stage<KB, VB> st[kDepth];
     int it[kDepth];
+    // Past the end a wave re-reads the last tile (cache hit) and processes it as a dead tile: the load
+    // stream and the loop body stay uniform, which keeps the outstanding-load accounting exact.
 #pragma unroll
     for (int s = 0; s < kDepth; s++) {
       it[s] = grab();
-      // past the end: re-read the last tile (cache hit) so that the load stream stays uniform
       st[s].load(a, tile_base + (size_t)(it[s] < p_end ? it[s] : p_end - 1), lane);
     }
-    bool more = true;
-    while (more) {
+    while (it[0] < p_end) {      // a wave's items increase: it[0] is the oldest one in flight
 #pragma unroll
       for (int s = 0; s < kDepth; s++) {
-        if (more && it[s] < p_end) {
-          process(st[s]);
-          it[s] = grab();
-          st[s].load(a, tile_base + (size_t)(it[s] < p_end ? it[s] : p_end - 1), lane);
-        } else {
-          more = false;
-        }
+        const int nxt = grab();
+        if (it[s] < p_end) process(st[s], true);   // past the end: skip the work, keep the load stream
+        it[s] = nxt;
+        st[s].load(a, tile_base + (size_t)(nxt < p_end ? nxt : p_end - 1), lane);
       }
     }
   }
@@ -525,10 +537,10 @@ __global__ __launch_bounds__(kThreads) void decode_attn_kernel(AttnArgs a) {
 template <int KB, int VB>
 hipError_t launch_g(const AttnArgs& a, int G, dim3 grid, hipStream_t s) {
   switch (G) {
-    case 1: decode_attn_kernel<KB, VB, 1><<<grid, kThreads, 0, s>>>(a); break;
-    case 2: decode_attn_kernel<KB, VB, 2><<<grid, kThreads, 0, s>>>(a); break;
-    case 4: decode_attn_kernel<KB, VB, 4><<<grid, kThreads, 0, s>>>(a); break;
-    case 8: decode_attn_kernel<KB, VB, 8><<<grid, kThreads, 0, s>>>(a); break;
+    case 1: decode_attn_kernel<KB, VB, 1><<<grid, waves_for(1) * kWave, 0, s>>>(a); break;
+    case 2: decode_attn_kernel<KB, VB, 2><<<grid, waves_for(2) * kWave, 0, s>>>(a); break;
+    case 4: decode_attn_kernel<KB, VB, 4><<<grid, waves_for(4) * kWave, 0, s>>>(a); break;
+    case 8: decode_attn_kernel<KB, VB, 8><<<grid, waves_for(8) * kWave, 0, s>>>(a); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
@@ -536,7 +548,7 @@ hipError_t launch_g(const AttnArgs& a, int G, dim3 grid, hipStream_t s) {
 
 }  // namespace
 
-int attn_threads() { return kThreads; }
+int attn_threads() { return waves_for(1) * kWave; }
 
 hipError_t launch_decode_attn(const AttnArgs& a, int k_bits, int v_bits, int G, int units, hipStream_t s) {
   const dim3 grid(a.n_splits, units);
