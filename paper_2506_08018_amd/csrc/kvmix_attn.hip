@@ -52,27 +52,31 @@ __device__ __forceinline__ void wave_lds_fence() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// bit position (inside a 16-bit half, after the unpack shift) of the field that feeds slot
-// `s` (0..3 = slot % 4): the MFMA sees code * 2^(pos - 24).
-template <int BITS> __device__ __forceinline__ constexpr int field_pos(int s) { return BITS == 4 ? 4 * (s & 1) : 2 * s; }
+// Bit position (inside a 16-bit half, after the unpack shift) of the field that feeds slot `s`
+// (0..3 = slot % 4): the MFMA sees code * 2^(pos - 24). Fields are moved as high in the fp16 mantissa
+// as they fit: the matrix core aligns the products of one dot product to their largest nominal
+// exponent (that of a subnormal is fixed) and truncates below its window, so a code sitting in the
+// lowest mantissa bits loses product bits (measured: ~1e-5 relative at position 0, exact from 6 up).
+template <int BITS> __device__ __forceinline__ constexpr int field_pos(int s) { return BITS == 4 ? 4 * (s & 1) + 2 : 2 * s + 2; }
 
-// ---- A operands from packed words. w: the lane's words of the code plane(s).
-// 2-bit plane (also the low plane of 3-bit): 4 words, slot field at bits 2*slot of each half.
-__device__ __forceinline__ half8_t unpack2(const u32x4_t& w, const u32x4_t& w8, int slot) {
-  const uint32_t mask = 0x00030003u << (2 * (slot & 3));
-  const u32x4_t src = (slot & 4) ? w8 : w;
+// ---- A operands from packed words. wa = word << 2, wb = word >> 6 (slots 0..3 / 4..7 of each half).
+// 2-bit plane (also the low plane of 3-bit): slot field from bits 2*slot to bits 2*(slot%4) + 2.
+__device__ __forceinline__ half8_t unpack2(const u32x4_t& wa, const u32x4_t& wb, int slot) {
+  const uint32_t mask = 0x00030003u << (2 * (slot & 3) + 2);
+  const u32x4_t src = (slot & 4) ? wb : wa;
   return as_half8(src & mask);
 }
-// 4-bit: 8 words (two chunks of 4), slot -> chunk slot/4, field slot%4 at bits 4*field.
-__device__ __forceinline__ half8_t unpack4(const u32x4_t& w, const u32x4_t& w8, int field) {
-  const uint32_t mask = 0x000F000Fu << (4 * (field & 1));
-  const u32x4_t src = (field & 2) ? w8 : w;
+// 4-bit: 8 words (two chunks of 4), slot -> chunk slot/4, field slot%4 from bits 4*field to 4*(field%2) + 2.
+__device__ __forceinline__ half8_t unpack4(const u32x4_t& wa, const u32x4_t& wb, int field) {
+  const uint32_t mask = 0x000F000Fu << (4 * (field & 1) + 2);
+  const u32x4_t src = (field & 2) ? wb : wa;
   return as_half8(src & mask);
 }
 // 1-bit high plane of 3-bit codes: 2 words; word j/2 holds, for pair j, bit 8*(j%2) + 2*(slot%4) + slot/4.
-// hs[v] = plane shifted so that variant v = 2*(j%2) + slot/4 has its bits at 2*(slot%4) + 2.
+// hs[v] = plane shifted so that variant v = 2*(j%2) + slot/4 has its bits at 2*(slot%4) + 4, two above
+// the low plane's field (bit 10, the lowest exponent bit, continues the subnormal scale: 2^-14).
 __device__ __forceinline__ half8_t unpack1(const u32x2_t (&hs)[4], int slot) {
-  const uint32_t mask = 0x00010001u << (2 * (slot & 3) + 2);
+  const uint32_t mask = 0x00010001u << (2 * (slot & 3) + 4);
   const int hi = slot >> 2;
   u32x4_t r;
   r[0] = hs[0 + hi][0] & mask;   // j = 0: word 0, variant (0, hi)
@@ -82,61 +86,88 @@ __device__ __forceinline__ half8_t unpack1(const u32x2_t (&hs)[4], int slot) {
   return as_half8(r);
 }
 __device__ __forceinline__ void shift_hi_plane(const u32x2_t& h, u32x2_t (&hs)[4]) {
-  hs[0] = h << 2;   // (j%2 = 0, slot/4 = 0): source bit 2*s     -> 2*s + 2
-  hs[1] = h << 1;   // (0, 1):                 source bit 2*s + 1 -> 2*s + 2
-  hs[2] = h >> 6;   // (1, 0):                 source bit 2*s + 8 -> 2*s + 2
-  hs[3] = h >> 7;   // (1, 1):                 source bit 2*s + 9 -> 2*s + 2
+  hs[0] = h << 4;   // (j%2 = 0, slot/4 = 0): source bit 2*s     -> 2*s + 4
+  hs[1] = h << 3;   // (0, 1):                 source bit 2*s + 1 -> 2*s + 4
+  hs[2] = h >> 4;   // (1, 0):                 source bit 2*s + 8 -> 2*s + 4
+  hs[3] = h >> 5;   // (1, 1):                 source bit 2*s + 9 -> 2*s + 4
+}
+
+// Tile loads are buffer loads: a unit's array is one buffer resource (scalar registers), the tile's
+// byte offset a scalar operand and the lane's offset one 32-bit vector register, so a load costs no
+// address arithmetic. Reads beyond the resource's size return zero instead of faulting.
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+__device__ __forceinline__ rsrc_t make_rsrc(const void* base, uint32_t bytes) {
+  // the base is wave-uniform by construction; saying so keeps the descriptor in scalar registers
+  const uint64_t v = reinterpret_cast<uint64_t>(base);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+  void* ub = reinterpret_cast<void*>(((uint64_t)hi << 32) | lo);
+  return __builtin_amdgcn_make_buffer_rsrc(ub, 0, (int)__builtin_amdgcn_readfirstlane(bytes), 0x00020000);
+}
+__device__ __forceinline__ u32x4_t buf_load16(rsrc_t r, uint32_t voff, uint32_t soff) {
+  return __builtin_bit_cast(u32x4_t, __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, (int)soff, 0));
+}
+__device__ __forceinline__ u32x2_t buf_load8(rsrc_t r, uint32_t voff, uint32_t soff) {
+  return __builtin_bit_cast(u32x2_t, __builtin_amdgcn_raw_buffer_load_b64(r, (int)voff, (int)soff, 0));
+}
+__device__ __forceinline__ uint32_t buf_load4(rsrc_t r, uint32_t voff, uint32_t soff) {
+  return (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(r, (int)voff, (int)soff, 0);
 }
 
 // The lane's share of one packed tile as loaded (Raw) and prepared for unpacking (Codes).
 template <int BITS> struct Raw;
 template <> struct Raw<2> {
   u32x4_t w;
-  __device__ __forceinline__ void load(const uint32_t* tile, int lane) { w = *reinterpret_cast<const u32x4_t*>(tile + 4 * lane); }
+  __device__ __forceinline__ void load(rsrc_t r, uint32_t soff, uint32_t l16, uint32_t) { w = buf_load16(r, l16, soff); }
 };
 template <> struct Raw<3> {
   u32x4_t w; u32x2_t h;
-  __device__ __forceinline__ void load(const uint32_t* tile, int lane) {
-    w = *reinterpret_cast<const u32x4_t*>(tile + 4 * lane);
-    h = *reinterpret_cast<const u32x2_t*>(tile + 256 + 2 * lane);
+  __device__ __forceinline__ void load(rsrc_t r, uint32_t soff, uint32_t l16, uint32_t l8) {
+    w = buf_load16(r, l16, soff);
+    h = buf_load8(r, l8, soff + 1024u);
   }
 };
 template <> struct Raw<4> {
   u32x4_t w[2];
-  __device__ __forceinline__ void load(const uint32_t* tile, int lane) {
-    w[0] = *reinterpret_cast<const u32x4_t*>(tile + 4 * lane);
-    w[1] = *reinterpret_cast<const u32x4_t*>(tile + 256 + 4 * lane);
+  __device__ __forceinline__ void load(rsrc_t r, uint32_t soff, uint32_t l16, uint32_t) {
+    w[0] = buf_load16(r, l16, soff);
+    w[1] = buf_load16(r, l16, soff + 1024u);
   }
 };
 template <int BITS> struct Codes;
 template <> struct Codes<2> {
-  u32x4_t w, w8;
-  __device__ __forceinline__ explicit Codes(const Raw<2>& r) : w(r.w), w8(r.w >> 8) {}
-  __device__ __forceinline__ half8_t lo(int slot) const { return unpack2(w, w8, slot); }
+  u32x4_t wa, wb;
+  __device__ __forceinline__ explicit Codes(const Raw<2>& r) : wa(r.w << 2), wb(r.w >> 6) {}
+  __device__ __forceinline__ half8_t lo(int slot) const { return unpack2(wa, wb, slot); }
 };
 template <> struct Codes<3> {
-  u32x4_t w, w8; u32x2_t hs[4];
-  __device__ __forceinline__ explicit Codes(const Raw<3>& r) : w(r.w), w8(r.w >> 8) { shift_hi_plane(r.h, hs); }
-  __device__ __forceinline__ half8_t lo(int slot) const { return unpack2(w, w8, slot); }
+  u32x4_t wa, wb; u32x2_t hs[4];
+  __device__ __forceinline__ explicit Codes(const Raw<3>& r) : wa(r.w << 2), wb(r.w >> 6) { shift_hi_plane(r.h, hs); }
+  __device__ __forceinline__ half8_t lo(int slot) const { return unpack2(wa, wb, slot); }
   __device__ __forceinline__ half8_t hi(int slot) const { return unpack1(hs, slot); }
 };
 template <> struct Codes<4> {
-  u32x4_t w[2], w8[2];
-  __device__ __forceinline__ explicit Codes(const Raw<4>& r) { w[0] = r.w[0]; w[1] = r.w[1]; w8[0] = r.w[0] >> 8; w8[1] = r.w[1] >> 8; }
-  __device__ __forceinline__ half8_t lo(int slot) const { return unpack4(w[slot >> 2], w8[slot >> 2], slot & 3); }
+  u32x4_t wa[2], wb[2];
+  __device__ __forceinline__ explicit Codes(const Raw<4>& r) { wa[0] = r.w[0] << 2; wa[1] = r.w[1] << 2; wb[0] = r.w[0] >> 6; wb[1] = r.w[1] >> 6; }
+  __device__ __forceinline__ half8_t lo(int slot) const { return unpack4(wa[slot >> 2], wb[slot >> 2], slot & 3); }
 };
+
+// Buffer resources of one unit's packed arrays (wave-uniform).
+struct UnitBufs { rsrc_t kc, ks, kz, vc, vs, vz; };
 
 // One tile in flight: codes plus the lane's two scales / zero-points of each array.
 template <int KB, int VB> struct Stage {
   Raw<KB> kc; Raw<VB> vc;
   uint32_t ks, kz, vs, vz;
-  __device__ __forceinline__ void load(const AttnArgs& a, size_t tile, int lane) {
-    kc.load(a.k_codes + tile * tile_words(KB), lane);
-    ks = reinterpret_cast<const uint32_t*>(a.k_scale + tile * kD)[lane];
-    kz = reinterpret_cast<const uint32_t*>(a.k_zero + tile * kD)[lane];
-    vc.load(a.v_codes + tile * tile_words(VB), lane);
-    vs = reinterpret_cast<const uint32_t*>(a.v_scale + tile * kD)[lane];
-    vz = reinterpret_cast<const uint32_t*>(a.v_zero + tile * kD)[lane];
+  // t: tile index inside the unit (wave-uniform)
+  __device__ __forceinline__ void load(const UnitBufs& u, int t, int lane) {
+    const uint32_t l16 = 16u * lane, l8 = 8u * lane, l4 = 4u * lane;
+    const uint32_t ut = (uint32_t)t;
+    kc.load(u.kc, ut * (uint32_t)(tile_words(KB) * 4), l16, l8);
+    ks = buf_load4(u.ks, l4, ut * (uint32_t)(kD * 2));
+    kz = buf_load4(u.kz, l4, ut * (uint32_t)(kD * 2));
+    vc.load(u.vc, ut * (uint32_t)(tile_words(VB) * 4), l16, l8);
+    vs = buf_load4(u.vs, l4, ut * (uint32_t)(kD * 2));
+    vz = buf_load4(u.vz, l4, ut * (uint32_t)(kD * 2));
   }
 };
 
@@ -325,7 +356,17 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
   }
 
   // ---- packed tiles: kDepth tiles in flight per wave, taken from the workgroup's counter
-  const size_t tile_base = (size_t)u * a.tiles_cap;
+  UnitBufs up;
+  {
+    const size_t tile_base = (size_t)u * a.tiles_cap;
+    const uint32_t nt = (uint32_t)a.tiles_cap;
+    up.kc = make_rsrc(reinterpret_cast<const char*>(a.k_codes) + tile_base * (tile_words(KB) * 4), nt * (uint32_t)(tile_words(KB) * 4));
+    up.vc = make_rsrc(reinterpret_cast<const char*>(a.v_codes) + tile_base * (tile_words(VB) * 4), nt * (uint32_t)(tile_words(VB) * 4));
+    up.ks = make_rsrc(reinterpret_cast<const char*>(a.k_scale) + tile_base * (kD * 2), nt * (uint32_t)(kD * 2));
+    up.kz = make_rsrc(reinterpret_cast<const char*>(a.k_zero) + tile_base * (kD * 2), nt * (uint32_t)(kD * 2));
+    up.vs = make_rsrc(reinterpret_cast<const char*>(a.v_scale) + tile_base * (kD * 2), nt * (uint32_t)(kD * 2));
+    up.vz = make_rsrc(reinterpret_cast<const char*>(a.v_zero) + tile_base * (kD * 2), nt * (uint32_t)(kD * 2));
+  }
   auto grab = [&]() -> int {
     int it = 0;
     if (lane == 0) it = atomicAdd(&s_next, 1);
@@ -378,7 +419,8 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
     // Reference maximum from the hi column (the lo column changes a score by < 2^-10 of its size, which a
     // reference does not need); lo lanes take their partner's value so that a column pair stays in step.
     float mx = max8(x) * c_code + zt;
-    mx = lo_part ? ror8(mx) : mx;
+    const float mx_partner = ror8(mx);        // cross-lane read outside any divergent branch: all lanes must take part
+    mx = lo_part ? mx_partner : mx;
     raise_reference(live ? mx : -INFINITY);
     const float off_col = zt - mref;          // meaningful in hi lanes: score = sum * c_code + off_col + reference
 
@@ -441,7 +483,7 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
 #pragma unroll
     for (int s = 0; s < kDepth; s++) {
       it[s] = grab();
-      st[s].load(a, tile_base + (size_t)(it[s] < p_end ? it[s] : p_end - 1), lane);
+      st[s].load(up, it[s] < p_end ? it[s] : p_end - 1, lane);
     }
     while (it[0] < p_end) {      // a wave's items increase: it[0] is the oldest one in flight
 #pragma unroll
@@ -449,7 +491,7 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
         const int nxt = grab();
         if (it[s] < p_end) process(st[s], true);   // past the end: skip the work, keep the load stream
         it[s] = nxt;
-        st[s].load(a, tile_base + (size_t)(nxt < p_end ? nxt : p_end - 1), lane);
+        st[s].load(up, nxt < p_end ? nxt : p_end - 1, lane);
       }
     }
   }

@@ -19,7 +19,7 @@ def test_all_bit_combos(kb, vb, G):
     st, want = rc.decode_attn(u16(q))
     assert st == 0
     got = run_attn(gc, shape, cfg, q)
-    assert_attn_close(got, want, f"kb={kb} vb={vb} G={G}")
+    assert_attn_close(got, want, f"kb={kb} vb={vb} G={G}", tight=True)
 
 
 @pytest.mark.parametrize("G", [1, 2, 4, 8])
@@ -29,7 +29,7 @@ def test_gqa_groups_and_scale(G):
     for scale in (0.0, 0.05):
         st, want = rc.decode_attn(u16(q), scale)
         got = run_attn(gc, shape, cfg, q, softmax_scale=scale)
-        assert_attn_close(got, want, f"G={G} scale={scale}")
+        assert_attn_close(got, want, f"G={G} scale={scale}", tight=True)
 
 
 @pytest.mark.parametrize("n_splits", [1, 2, 3, 5, 8])
@@ -38,9 +38,9 @@ def test_result_independent_of_split_count(n_splits):
     q, k, v, rc, gc, shape, cfg = make_pair(2, 8, 2, 32 * 33 + 5, 64, 3, 4, seed=400)
     st, want = rc.decode_attn(u16(q))
     got = run_attn(gc, shape, cfg, q, n_splits=n_splits)
-    assert_attn_close(got, want, f"splits={n_splits}")
+    assert_attn_close(got, want, f"splits={n_splits}", tight=True)
     again = run_attn(gc, shape, cfg, q, n_splits=n_splits)   # counters were reset: second call still right
-    assert_attn_close(again, want, f"splits={n_splits} (second call)")
+    assert_attn_close(again, want, f"splits={n_splits} (second call)", tight=True)
 
 
 @pytest.mark.parametrize("kb,vb,G", [(16, 16, 1), (16, 16, 4), (2, 2, 2)])
@@ -126,6 +126,17 @@ def test_append_and_flush_match_oracle(kb, vb, G):
     assert np.array_equal(bits_of(gc.v_win, np.uint16).reshape(rc.v_win.shape), rc.v_win)
 
 
+@pytest.mark.parametrize("kb,vb,G", [(2, 2, 1), (3, 4, 4), (4, 2, 8)])
+def test_many_tiles_per_wave(kb, vb, G):
+    """Long context in few workgroups: every wave runs many iterations of its prefetch loop."""
+    print(f"case many tiles kb={kb} vb={vb} G={G}", flush=True)
+    q, k, v, rc, gc, shape, cfg = make_pair(1, 2 * G, 2, 32 * 150 + 77, 128, kb, vb, seed=900 + G)
+    st, want = rc.decode_attn(u16(q))
+    for ns in (1, 2):
+        for rep in range(2):
+            assert_attn_close(run_attn(gc, shape, cfg, q, n_splits=ns), want, f"many tiles splits={ns} rep={rep}", tight=True)
+
+
 def test_config1_full_parity():
     """BASELINE config 1 in full: 1 layer, B1, 32 heads, T1024, window 32, K2/V2."""
     print("case config1", flush=True)
@@ -135,7 +146,7 @@ def test_config1_full_parity():
     assert_cache_equal(rc, gc)
     st, want = rc.decode_attn(u16(q))
     for ns in (0, 1, 4):
-        assert_attn_close(run_attn(gc, shape, cfg, q, n_splits=ns), want, f"config1 splits={ns}")
+        assert_attn_close(run_attn(gc, shape, cfg, q, n_splits=ns), want, f"config1 splits={ns}", tight=True)
 
 
 def test_attn_error_returns():
