@@ -110,6 +110,9 @@ def main():
     ap.add_argument("--seed", type=int, default=synth.BASE_SEED)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--n-splits", type=int, default=0)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy (known size) so that rocprofv3 FETCH_SIZE / WRITE_SIZE "
+                         "readings of the attention kernel can be scaled by what the same counters read for it")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (every unit = (layer, batch, kv head) is independent; "
@@ -170,6 +173,14 @@ def main():
     layer_bytes = [algorithmic_bytes(units, ly["cache"].n_q, ly["cache"].n_w, ly["cfg"].k_bits, ly["cfg"].v_bits) for ly in layers]
     bytes_per_launch = float(np.mean(layer_bytes))
     achieved = bytes_per_launch / (launch_us * 1e-6) / 1e9
+
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=device)   # 1 GiB read, 1 GiB written per call
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.mul(src, 1.0, out=dst)       # an elementwise kernel (a plain copy_ would be a DMA transfer)
+        torch.cuda.synchronize()
+        del src, dst
 
     result = {
         "metric": "decode-attn tokens/s over mixed-bit KV; achieved HBM GB/s vs MI355X peak",
