@@ -1,0 +1,54 @@
+"""GPU parity at the full sizes of the benchmark configurations, in the launch configuration bench.py times
+(library-chosen split count): one layer per (K bits, V bits) pair, sampled units checked against the oracle
+(codes bit-exact for the unit's packed tiles, attention outputs within the benchmark spec's bound)."""
+import numpy as np
+import pytest
+
+import kvmix_synth as synth
+from gpu_common import assert_attn_close, bits_of, t16, u16
+
+pytestmark = pytest.mark.gpu
+
+CASES = [("cfg2_llama2_7b", 16), ("cfg3_mistral_7b_gqa", 16), ("cfg4_llama3_8b_long", 4), ("cfg5_70b_stress", 16)]
+
+
+@pytest.mark.parametrize("name,n_sample", CASES)
+def test_full_size_sampled_units(name, n_sample):
+    import torch
+    import paper_2506_08018_amd as kv
+    from oracle.kvmix_ref import RefCache
+    c = synth.CONFIGS[name]
+    B, Hq, Hkv, T, W = c["B"], c["Hq"], c["Hkv"], c["T"], c["W"]
+    G = Hq // Hkv
+    n_q = (T - W) // 32 * 32
+    shape = kv.Shape(B, Hq, Hkv)
+    ws = torch.zeros(kv.workspace_bytes(shape, T), dtype=torch.uint8, device="cuda")
+    rng = np.random.default_rng(7)
+    for layer, (kb, vb) in enumerate([(2, 2), (3, 2), (2, 4), (3, 4)]):
+        print(f"case {name} layer {layer} bits {kb}/{vb}", flush=True)
+        cfg = kv.LayerCfg(kb, vb, W)
+        q, k, v = synth.gen_layer_torch("cuda", synth.BASE_SEED, layer, B, Hq, Hkv, T)
+        gc = kv.LayerCache(shape, cfg, n_q, W + 32)
+        kv.quantize_pack(shape, cfg, k[:, :, :n_q], v[:, :, :n_q], gc)
+        gc.set_window(k[:, :, n_q:], v[:, :, n_q:])
+        out = torch.zeros_like(q)
+        kv.decode_attn(shape, cfg, q, gc, out, ws)
+        torch.cuda.synchronize()
+        assert not ws[: 4 * shape.units].any()
+        units = rng.choice(B * Hkv, min(n_sample, B * Hkv), replace=False)
+        tiles = n_q // 32
+        kcodes = gc.k_codes.view(torch.int32).view(B * Hkv, tiles, -1)
+        vcodes = gc.v_codes.view(torch.int32).view(B * Hkv, tiles, -1)
+        for u in units:
+            b, j = divmod(int(u), Hkv)
+            ku, vu = t16(k[b, j]).reshape(1, 1, T, 128), t16(v[b, j]).reshape(1, 1, T, 128)
+            qu = t16(q[b, j * G:(j + 1) * G]).reshape(1, G, 128)
+            rc = RefCache(1, G, 1, kb, vb, W, n_q, W + 32)
+            assert rc.quantize_pack(ku[:, :, :n_q], vu[:, :, :n_q]) == 0
+            rc.set_window(ku[:, :, n_q:], vu[:, :, n_q:])
+            assert np.array_equal(kcodes[u].cpu().numpy().view(np.uint32), rc.k_codes[0]), f"K codes of unit {u}"
+            assert np.array_equal(vcodes[u].cpu().numpy().view(np.uint32), rc.v_codes[0]), f"V codes of unit {u}"
+            st, want = rc.decode_attn(qu)
+            assert st == 0
+            assert_attn_close(t16(out[b, j * G:(j + 1) * G]).reshape(1, G, 128), want, f"{name} unit {u} bits {kb}/{vb}", tight=True)
+        del q, k, v, gc, out
