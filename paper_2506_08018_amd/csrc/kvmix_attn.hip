@@ -562,14 +562,32 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
     const int hh = idx / kD, d = idx % kD;
     const float* base = a.part + ((size_t)u * a.n_splits * G + hh) * (kD + 2);
     const size_t stride = (size_t)G * (kD + 2);
-    float M = -INFINITY;
-    for (int s = 0; s < a.n_splits; s++) M = fmaxf(M, ld_agent(base + s * stride));
-    float Lsum = 0.0f, O = 0.0f;
-    for (int s = 0; s < a.n_splits; s++) {
-      const float ms = ld_agent(base + s * stride);
-      const float f = (ms == -INFINITY) ? 0.0f : fast_exp2(ms - M);
-      Lsum += ld_agent(base + s * stride + 1) * f;
-      O += ld_agent(base + s * stride + 2 + d) * f;
+    // one pass, eight splits per round trip: the loads of a batch are issued together
+    float M = -INFINITY, Lsum = 0.0f, O = 0.0f;
+    for (int s0 = 0; s0 < a.n_splits; s0 += 8) {
+      float ms[8], ls[8], os[8];
+#pragma unroll
+      for (int k = 0; k < 8; k++) {
+        const bool in = s0 + k < a.n_splits;
+        const float* pp = base + (size_t)(in ? s0 + k : s0) * stride;
+        ms[k] = ld_agent(pp);
+        ls[k] = ld_agent(pp + 1);
+        os[k] = ld_agent(pp + 2 + d);
+        if (!in) ms[k] = -INFINITY;
+      }
+      float Mn = M;
+#pragma unroll
+      for (int k = 0; k < 8; k++) Mn = fmaxf(Mn, ms[k]);
+      const float fold = (M == -INFINITY) ? 0.0f : fast_exp2(M - Mn);
+      Lsum *= fold;
+      O *= fold;
+#pragma unroll
+      for (int k = 0; k < 8; k++) {
+        const float f = (ms[k] == -INFINITY) ? 0.0f : fast_exp2(ms[k] - Mn);
+        Lsum += ls[k] * f;
+        O += os[k] * f;
+      }
+      M = Mn;
     }
     a.out[((size_t)b * a.Hq + (size_t)jh * G + hh) * kD + d] = __builtin_bit_cast(uint16_t, (half_t)(O / Lsum));
   }
