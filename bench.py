@@ -25,7 +25,7 @@ import kvmix_synth as synth  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per attention launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/); None = not measured
-MEASURED_TRAFFIC_BYTES = None
+MEASURED_TRAFFIC_BYTES = 127.08e6   # cfg2_llama2_7b, layer-weighted: 2.0 x FETCH_SIZE + 1.0 x WRITE_SIZE
 
 
 def algorithmic_bytes(units, n_q, n_w, kb, vb):
@@ -199,7 +199,8 @@ def main():
         "attn_only_ms_per_step": attn_ms,
         "attn_only_tokens_per_s": B / (attn_ms * 1e-3),
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES,
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": MEASURED_TRAFFIC_BYTES if args.config == "cfg2_llama2_7b" else None,
                      "kernel": "decode_attn_kernel", "bytes_per_launch": bytes_per_launch, "launch_us": launch_us,
                      "launches_timed": args.steps * L},
     }
