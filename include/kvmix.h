@@ -26,23 +26,28 @@
  *   - D = 128 and group = 32 are the only supported head dimension / group size
  *     (the paper's setting, Sec. 4.2).
  *
- * Packed cache layout (per layer; all arrays unit-major, then 32-token tile-major)
+ * Packed cache layout (per layer): one buffer `packed` of [units][T_cap/32] tile records
  *   A "tile" is 32 consecutive tokens x 128 channels of one unit. Token index inside the tile
  *   tau = 0..31, channel d = 0..127.
  *   Keys are quantized per channel: a group is the 32 tokens of a tile for one channel
  *   (Sec. 3.2.1: tensor viewed as [B*nh*D, T], cut into groups of 32 along T).
  *   Values are quantized per token: a group is 32 consecutive channels of one token, g = d/32.
- *   k_scale/k_zero : [units][T_cap/32][128] fp16   (scale s and group minimum per channel)
- *   v_scale/v_zero : [units][T_cap/32][4][32] fp16  (index [g][tau] inside the tile)
- *   k_codes/v_codes: [units][T_cap/32][128*bits] uint32 words; the bit position of every code
- *   inside its tile is given below. "lane" l = 0..63 names the 16-byte column of a 1 KiB
- *   block, l = 16*kq + i.
+ *   Everything a tile needs is contiguous: its record is 256 + 128*k_bits + 128*v_bits 32-bit
+ *   words = [metadata: 256 words][Key codes: 128*k_bits words][Value codes: 128*v_bits words]
+ *   (3072 bytes for 2/2 bit, 5120 for 4/4). Record r = u*(T_cap/32) + tile starts at word
+ *   r * record_words.
+ *   Metadata. "lane" l = 0..63 names a 16-byte column; word 4*l + f holds two fp16 values, the
+ *   first in bits [0,16), the second in bits [16,32):
+ *     f = 0: Key scale s of channels 2l, 2l+1        f = 1: Key group minimum of the same two
+ *     f = 2: Value scale of groups (tau, g) = (2*(l%16), l/16) and (2*(l%16) + 1, l/16)
+ *     f = 3: Value group minimum of the same two groups
+ *   Codes. Inside its code section the position of every code is given below; l = 16*kq + i.
  *     Key code (tau, d):   ks = d/32, kq = (d%32)/8, j = (d%8)/2, hh = d%2,
  *                          m = (tau%8)/4, i = 4*(tau/8) + tau%4, slot = ks + 4*m
  *     Value code (tau, d): kq = tau/8, j = (tau%8)/2, hh = tau%2, i = d%16, slot = d/16
  *     2-bit: word 4*l + j, bits [16*hh + 2*slot, +2).
  *     4-bit: word 256*(slot/4) + 4*l + j, bits [16*hh + 4*(slot%4), +4).
- *     3-bit: code = lo + 4*hi. The 2-bit plane `lo` is stored exactly like a 2-bit tile
+ *     3-bit: code = lo + 4*hi. The 2-bit plane `lo` is stored exactly like a 2-bit section
  *            (256 words), followed by the 1-bit plane `hi` (128 words): word 256 + 2*l + j/2,
  *            bit 16*hh + 8*(j%2) + 2*(slot%4) + slot/4.
  *            The two elements of every group that the paper stores with 2 bits (in-group
@@ -96,8 +101,7 @@ typedef struct {
 
 /* One layer's cache: caller-owned device buffers, host-side counters. */
 typedef struct {
-  uint32_t* k_codes; uint16_t* k_scale; uint16_t* k_zero;
-  uint32_t* v_codes; uint16_t* v_scale; uint16_t* v_zero;
+  uint32_t* packed;  /* tile records (may be NULL when k_bits == 16) */
   uint16_t* k_win;   uint16_t* v_win;
   int32_t T_cap; /* capacity of the packed part in tokens, multiple of 32 */
   int32_t W_cap; /* window slots, multiple of 32, >= window + 32 */
@@ -111,11 +115,10 @@ const char* kvmix_strerror(int status);
 /* HIP error code (hipError_t as int) of the most recent KVMIX_ERR_HIP on this thread's process. */
 int kvmix_last_hip_error(void);
 
-/* Byte sizes of the eight cache arrays for capacities (T_cap, W_cap). Any output pointer may
- * be NULL. k/v_meta_b is the size of EACH of scale and zero; win_b of EACH of k_win, v_win. */
+/* Byte sizes of the cache buffers for capacities (T_cap, W_cap). Any output pointer may be
+ * NULL. packed_b is the size of `packed` (0 for 16 bit), win_b of EACH of k_win, v_win. */
 int kvmix_cache_bytes(const kvmix_shape* shape, const kvmix_layer_cfg* cfg, int T_cap, int W_cap,
-                      size_t* k_code_b, size_t* k_meta_b, size_t* v_code_b, size_t* v_meta_b,
-                      size_t* win_b);
+                      size_t* packed_b, size_t* win_b);
 
 /* Workspace needed by kvmix_decode_attn for any context up to T_max packed tokens (split
  * partials + arrival counters). The workspace must be zero-filled once before first use;
@@ -123,7 +126,7 @@ int kvmix_cache_bytes(const kvmix_shape* shape, const kvmix_layer_cfg* cfg, int 
 int kvmix_workspace_bytes(const kvmix_shape* shape, int T_max, size_t* bytes);
 
 /* Part 1 (Sec. 3.2.2 steps 1-4, Sec. 3.4 item 1). Quantize n_tokens (multiple of 32) fp16
- * tokens of K and V and write codes/scales/zeros into the packed cache at token offset t0
+ * tokens of K and V and write codes, scales and minima into the tile records at token offset t0
  * (multiple of 32, t0 + n_tokens <= T_cap). Element (b, j, t, d) of k_fp16 / v_fp16 is at
  * index b*batch_stride + j*head_stride + t*token_stride + d (strides in elements, multiples
  * of 8). Per group: mn/mx by fp16 comparison; s = fp16((mx - mn) / qmax) with fp32

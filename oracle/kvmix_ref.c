@@ -9,7 +9,8 @@
  *   - the group-wise asymmetric quantizer of Sec. 3.2.2 (steps 1-4 and the q_max case
  *     equation for 3-bit blocks of 11), with Keys grouped per channel and Values per token
  *     (Sec. 3.2.1), group size 32 (Sec. 4.2);
- *   - the packed-cache encoding (bit positions documented in pos_key / pos_value below);
+ *   - the packed-cache encoding (bit positions documented in pos_key / pos_value, the tile
+ *     record in the section "tile records" below);
  *   - decode attention by its plain definition: softmax(scale * q K~^T) V~ in fp64, where
  *     K~, V~ are the dequantized packed tokens (x = q*s + min, Sec. 3.2.2 step 4) followed by
  *     the fp16 recent window (Sec. 3.3). The fused kernel of Sec. 3.4 item 2 reaches exactly
@@ -45,8 +46,7 @@ enum { REF_OK = 0, REF_ERR_NULL = -1, REF_ERR_BAD_BITS = -2, REF_ERR_BAD_GROUP =
 typedef struct { int32_t B, Hq, Hkv, D, group; } ref_shape;
 typedef struct { int32_t k_bits, v_bits, window; } ref_layer_cfg;
 typedef struct {
-  uint32_t* k_codes; uint16_t* k_scale; uint16_t* k_zero;
-  uint32_t* v_codes; uint16_t* v_scale; uint16_t* v_zero;
+  uint32_t* packed;  /* tile records, see record_of() */
   uint16_t* k_win;   uint16_t* v_win;
   int32_t T_cap, W_cap, n_q, n_w, w0;
 } ref_layer_cache; /* all pointers are host memory */
@@ -195,6 +195,39 @@ void kvmix_ref_unpack_tile(int which, int bits, const uint32_t* tile, uint8_t* c
       codes[tau * D_HEAD + d] = (uint8_t)get_code(tile, bits, which ? pos_value(bits, tau, d) : pos_key(bits, tau, d));
 }
 
+/* ------------------------------------------------------------------ tile records
+ * All data of one tile is one contiguous record of 32-bit words:
+ *   [0, 256)                      metadata
+ *   [256, 256 + 128 kb)           Key codes (tile words as above)
+ *   [256 + 128 kb, + 128 vb)      Value codes
+ * Metadata word 4 l + f (l = 0..63) carries two fp16 patterns, "first" in its low 16 bits:
+ *   f = 0 / 1: scale / minimum of the Key groups of channels 2l (first) and 2l + 1 (second)
+ *   f = 2 / 3: scale / minimum of the Value groups (token 2 (l%16), block l/16) (first) and
+ *              (token 2 (l%16) + 1, block l/16) (second)                                         */
+#define META_WORDS 256
+
+int kvmix_ref_record_words(int kb, int vb) { return META_WORDS + words_per_tile(kb) + words_per_tile(vb); }
+
+static uint32_t* record_of(const ref_layer_cache* c, int kb, int vb, int u, int tile) {
+  size_t r = (size_t)u * (size_t)(c->T_cap / TILE_TOKENS) + (size_t)tile;
+  return c->packed + r * (size_t)kvmix_ref_record_words(kb, vb);
+}
+static uint32_t* key_codes_of(uint32_t* rec) { return rec + META_WORDS; }
+static uint32_t* value_codes_of(uint32_t* rec, int kb) { return rec + META_WORDS + words_per_tile(kb); }
+
+static void meta_store(uint32_t* rec, int word, int second, uint16_t v) {
+  uint32_t keep = second ? 0x0000FFFFu : 0xFFFF0000u;
+  rec[word] = (rec[word] & keep) | ((uint32_t)v << (second ? 16 : 0));
+}
+static uint16_t meta_fetch(const uint32_t* rec, int word, int second) {
+  return (uint16_t)(rec[word] >> (second ? 16 : 0));
+}
+/* f = 0 scale, 1 minimum */
+static void key_meta_store(uint32_t* rec, int d, int f, uint16_t v) { meta_store(rec, 4 * (d / 2) + f, d % 2, v); }
+static uint16_t key_meta_fetch(const uint32_t* rec, int d, int f) { return meta_fetch(rec, 4 * (d / 2) + f, d % 2); }
+static void value_meta_store(uint32_t* rec, int tau, int g, int f, uint16_t v) { meta_store(rec, 4 * (16 * g + tau / 2) + 2 + f, tau % 2, v); }
+static uint16_t value_meta_fetch(const uint32_t* rec, int tau, int g, int f) { return meta_fetch(rec, 4 * (16 * g + tau / 2) + 2 + f, tau % 2); }
+
 /* ------------------------------------------------------------------ cache-level calls */
 
 static int check_common(const ref_shape* sh, const ref_layer_cfg* cfg) {
@@ -221,7 +254,7 @@ static int quantize_pack_strided(const ref_shape* sh, const ref_layer_cfg* cfg, 
                                  int64_t k_tok, int64_t k_chan, int64_t k_unit_b, int64_t k_unit_h,
                                  int64_t v_tok, int64_t v_chan, int64_t v_unit_b, int64_t v_unit_h,
                                  int n_tokens, int t0, const ref_layer_cache* c) {
-  int units = sh->B * sh->Hkv, tiles_cap = c->T_cap / TILE_TOKENS;
+  int units = sh->B * sh->Hkv;
   int kb = cfg->k_bits, vb = cfg->v_bits;
 #pragma omp parallel for schedule(static)
   for (int u = 0; u < units; u++) {
@@ -229,25 +262,28 @@ static int quantize_pack_strided(const ref_shape* sh, const ref_layer_cfg* cfg, 
     const uint16_t* ku = k + b * k_unit_b + j * k_unit_h;
     const uint16_t* vu = v + b * v_unit_b + j * v_unit_h;
     for (int tt = 0; tt < n_tokens / TILE_TOKENS; tt++) {
-      size_t tile = (size_t)u * tiles_cap + (size_t)(t0 / TILE_TOKENS + tt);
+      uint32_t* rec = record_of(c, kb, vb, u, t0 / TILE_TOKENS + tt);
       uint8_t codes[TILE_TOKENS * D_HEAD];
-      uint16_t x[GROUP]; uint8_t gc[GROUP];
+      uint16_t x[GROUP]; uint8_t gc[GROUP]; uint16_t s_h, z_h;
       /* Keys: one group per channel, along the 32 tokens of the tile (Sec. 3.2.1) */
       for (int d = 0; d < D_HEAD; d++) {
         for (int tau = 0; tau < TILE_TOKENS; tau++) x[tau] = ku[(int64_t)(tt * TILE_TOKENS + tau) * k_tok + d * k_chan];
-        kvmix_ref_quantize_group(x, kb, gc, &c->k_scale[tile * D_HEAD + d], &c->k_zero[tile * D_HEAD + d]);
+        kvmix_ref_quantize_group(x, kb, gc, &s_h, &z_h);
+        key_meta_store(rec, d, 0, s_h);
+        key_meta_store(rec, d, 1, z_h);
         for (int tau = 0; tau < TILE_TOKENS; tau++) codes[tau * D_HEAD + d] = gc[tau];
       }
-      kvmix_ref_pack_tile(0, kb, codes, c->k_codes + tile * words_per_tile(kb));
+      kvmix_ref_pack_tile(0, kb, codes, key_codes_of(rec));
       /* Values: one group per (token, 32-channel block) */
       for (int tau = 0; tau < TILE_TOKENS; tau++)
         for (int g = 0; g < D_HEAD / GROUP; g++) {
           for (int e = 0; e < GROUP; e++) x[e] = vu[(int64_t)(tt * TILE_TOKENS + tau) * v_tok + (g * GROUP + e) * v_chan];
-          size_t mi = tile * D_HEAD + (size_t)g * TILE_TOKENS + tau;   /* [tile][g][tau] */
-          kvmix_ref_quantize_group(x, vb, gc, &c->v_scale[mi], &c->v_zero[mi]);
+          kvmix_ref_quantize_group(x, vb, gc, &s_h, &z_h);
+          value_meta_store(rec, tau, g, 0, s_h);
+          value_meta_store(rec, tau, g, 1, z_h);
           for (int e = 0; e < GROUP; e++) codes[tau * D_HEAD + g * GROUP + e] = gc[e];
         }
-      kvmix_ref_pack_tile(1, vb, codes, c->v_codes + tile * words_per_tile(vb));
+      kvmix_ref_pack_tile(1, vb, codes, value_codes_of(rec, kb));
     }
   }
   return REF_OK;
@@ -297,22 +333,18 @@ int kvmix_ref_append(const ref_shape* sh, const ref_layer_cfg* cfg, const uint16
 }
 
 /* Dequantized packed tokens of one unit as binary64: out[t*128 + d], t < n_q. */
-static void dequant_unit(const ref_shape* sh, int bits, int which, const ref_layer_cache* c, int u, double* out) {
-  (void)sh;
-  int tiles_cap = c->T_cap / TILE_TOKENS;
-  const uint32_t* codes_base = which ? c->v_codes : c->k_codes;
-  const uint16_t* sc = which ? c->v_scale : c->k_scale;
-  const uint16_t* zr = which ? c->v_zero : c->k_zero;
+static void dequant_unit(const ref_layer_cfg* cfg, int which, const ref_layer_cache* c, int u, double* out) {
+  int kb = cfg->k_bits, vb = cfg->v_bits, bits = which ? vb : kb;
   uint8_t codes[TILE_TOKENS * D_HEAD];
   for (int tt = 0; tt < c->n_q / TILE_TOKENS; tt++) {
-    size_t tile = (size_t)u * tiles_cap + tt;
-    kvmix_ref_unpack_tile(which, bits, codes_base + tile * words_per_tile(bits), codes);
+    uint32_t* rec = record_of(c, kb, vb, u, tt);
+    kvmix_ref_unpack_tile(which, bits, which ? value_codes_of(rec, kb) : key_codes_of(rec), codes);
     for (int tau = 0; tau < TILE_TOKENS; tau++)
       for (int d = 0; d < D_HEAD; d++) {
-        size_t mi; int i;
-        if (which == 0) { mi = tile * D_HEAD + d; i = tau; }                       /* group along tokens */
-        else { mi = tile * D_HEAD + (size_t)(d / GROUP) * TILE_TOKENS + tau; i = d % GROUP; } /* along channels */
-        out[(size_t)(tt * TILE_TOKENS + tau) * D_HEAD + d] = kvmix_ref_dequant_elem(codes[tau * D_HEAD + d], i, bits, sc[mi], zr[mi]);
+        uint16_t s_h, z_h; int i;
+        if (which == 0) { s_h = key_meta_fetch(rec, d, 0); z_h = key_meta_fetch(rec, d, 1); i = tau; }   /* group along tokens */
+        else { s_h = value_meta_fetch(rec, tau, d / GROUP, 0); z_h = value_meta_fetch(rec, tau, d / GROUP, 1); i = d % GROUP; } /* along channels */
+        out[(size_t)(tt * TILE_TOKENS + tau) * D_HEAD + d] = kvmix_ref_dequant_elem(codes[tau * D_HEAD + d], i, bits, s_h, z_h);
       }
   }
 }
@@ -324,7 +356,7 @@ int kvmix_ref_dequant(const ref_shape* sh, const ref_layer_cfg* cfg, const ref_l
   if (cfg->k_bits == 16) return c->n_q == 0 ? REF_OK : REF_ERR_BAD_BITS;
   int units = sh->B * sh->Hkv;
   for (int u = 0; u < units; u++)
-    dequant_unit(sh, which ? cfg->v_bits : cfg->k_bits, which, c, u, out + (size_t)u * c->n_q * D_HEAD);
+    dequant_unit(cfg, which, c, u, out + (size_t)u * c->n_q * D_HEAD);
   return REF_OK;
 }
 
@@ -344,7 +376,7 @@ int kvmix_ref_decode_attn(const ref_shape* sh, const ref_layer_cfg* cfg, const u
     double* Kt = (double*)malloc(sizeof(double) * (size_t)T * D_HEAD);
     double* Vt = (double*)malloc(sizeof(double) * (size_t)T * D_HEAD);
     double* a = (double*)malloc(sizeof(double) * (size_t)T);
-    if (c->n_q) { dequant_unit(sh, cfg->k_bits, 0, c, u, Kt); dequant_unit(sh, cfg->v_bits, 1, c, u, Vt); }
+    if (c->n_q) { dequant_unit(cfg, 0, c, u, Kt); dequant_unit(cfg, 1, c, u, Vt); }
     for (int r = 0; r < c->n_w; r++) {                   /* window tokens, oldest first */
       int slot = (c->w0 + r) % W;
       for (int d = 0; d < D_HEAD; d++) {

@@ -22,9 +22,7 @@ class _Cfg(C.Structure):
 
 
 class _Cache(C.Structure):
-    _fields_ = [("k_codes", C.c_void_p), ("k_scale", C.c_void_p), ("k_zero", C.c_void_p),
-                ("v_codes", C.c_void_p), ("v_scale", C.c_void_p), ("v_zero", C.c_void_p),
-                ("k_win", C.c_void_p), ("v_win", C.c_void_p)] + \
+    _fields_ = [("packed", C.c_void_p), ("k_win", C.c_void_p), ("v_win", C.c_void_p)] + \
                [(n, C.c_int32) for n in ("T_cap", "W_cap", "n_q", "n_w", "w0")]
 
 
@@ -46,6 +44,8 @@ def lib():
         L.kvmix_ref_unpack_tile.restype = None
         L.kvmix_ref_unpack_tile.argtypes = [C.c_int, C.c_int, C.c_void_p, C.c_void_p]
         L.kvmix_ref_num_threads.restype = C.c_int
+        L.kvmix_ref_record_words.restype = C.c_int
+        L.kvmix_ref_record_words.argtypes = [C.c_int, C.c_int]
         L.kvmix_ref_quantize_pack.restype = C.c_int
         L.kvmix_ref_quantize_pack.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64,
                                               C.c_int64, C.c_int, C.c_int, C.c_void_p]
@@ -112,6 +112,30 @@ def unpack_tile(which, bits, tile):
     return codes
 
 
+def record_words(k_bits: int, v_bits: int) -> int:
+    return lib().kvmix_ref_record_words(int(k_bits), int(v_bits))
+
+
+def split_records(packed, k_bits, v_bits):
+    """Test helper: cut a buffer of tile records, uint32 [units][tiles][record words], into its fields by the
+    layout statement (metadata word 4l+f, first value in the low half): returns a dict with k_codes, v_codes
+    (uint32 [units][tiles][128*bits]), k_scale, k_zero (uint16 [units][tiles][128], by channel) and v_scale,
+    v_zero (uint16 [units][tiles][4][32], by [channel block][token]). Little-endian host."""
+    packed = np.ascontiguousarray(packed, dtype=np.uint32)
+    units, tiles, rw = packed.shape
+    assert rw == 256 + 128 * k_bits + 128 * v_bits
+    meta = np.ascontiguousarray(packed[:, :, :256])
+    lo = (meta & 0xFFFF).astype(np.uint16).reshape(units, tiles, 64, 4)     # first value of word 4l+f
+    hi = (meta >> 16).astype(np.uint16).reshape(units, tiles, 64, 4)        # second value
+    pair = np.stack([lo, hi], axis=-1)                                      # [u][t][l][f][first/second]
+    out = {"k_codes": packed[:, :, 256:256 + 128 * k_bits], "v_codes": packed[:, :, 256 + 128 * k_bits:]}
+    for f, name in enumerate(("k_scale", "k_zero")):
+        out[name] = pair[:, :, :, f, :].reshape(units, tiles, 128)          # channel 2l + second
+    for f, name in enumerate(("v_scale", "v_zero")):
+        out[name] = pair[:, :, :, 2 + f, :].reshape(units, tiles, 4, 32)    # l = 16g + tau/2, tau = 2(l%16) + second
+    return out
+
+
 class RefCache:
     """One layer's cache in host memory, driven through the oracle's cache-level calls."""
 
@@ -122,17 +146,22 @@ class RefCache:
         tiles = T_cap // 32
         kb = k_bits if k_bits != 16 else 2
         vb = v_bits if v_bits != 16 else 2
-        self.k_codes = np.zeros((self.units, tiles, 128 * kb), np.uint32)
-        self.v_codes = np.zeros((self.units, tiles, 128 * vb), np.uint32)
-        self.k_scale = np.zeros((self.units, tiles, 128), np.uint16)
-        self.k_zero = np.zeros((self.units, tiles, 128), np.uint16)
-        self.v_scale = np.zeros((self.units, tiles, 4, 32), np.uint16)
-        self.v_zero = np.zeros((self.units, tiles, 4, 32), np.uint16)
+        self.kb, self.vb = kb, vb
+        self.packed = np.zeros((self.units, tiles, record_words(kb, vb)), np.uint32)
         self.k_win = np.zeros((self.units, W_cap, 128), np.uint16)
         self.v_win = np.zeros((self.units, 128, W_cap), np.uint16)
-        self.c = _Cache(_ptr(self.k_codes).value, _ptr(self.k_scale).value, _ptr(self.k_zero).value,
-                        _ptr(self.v_codes).value, _ptr(self.v_scale).value, _ptr(self.v_zero).value,
-                        _ptr(self.k_win).value, _ptr(self.v_win).value, T_cap, W_cap, 0, 0, 0)
+        self.c = _Cache(_ptr(self.packed).value, _ptr(self.k_win).value, _ptr(self.v_win).value, T_cap, W_cap, 0, 0, 0)
+
+    def fields(self):
+        """The record buffer cut into codes / scales / minima (copies), see split_records."""
+        return split_records(self.packed, self.kb, self.vb)
+
+    k_codes = property(lambda self: self.fields()["k_codes"])
+    v_codes = property(lambda self: self.fields()["v_codes"])
+    k_scale = property(lambda self: self.fields()["k_scale"])
+    k_zero = property(lambda self: self.fields()["k_zero"])
+    v_scale = property(lambda self: self.fields()["v_scale"])
+    v_zero = property(lambda self: self.fields()["v_zero"])
 
     # counters live in the C struct
     n_q = property(lambda self: self.c.n_q)

@@ -29,7 +29,7 @@ class LayerCfg(C.Structure):
 
 
 class _CacheStruct(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in ("k_codes", "k_scale", "k_zero", "v_codes", "v_scale", "v_zero", "k_win", "v_win")] + \
+    _fields_ = [(n, C.c_void_p) for n in ("packed", "k_win", "v_win")] + \
                [(n, C.c_int32) for n in ("T_cap", "W_cap", "n_q", "n_w", "w0")]
 
 
@@ -47,7 +47,7 @@ def lib():
         L.kvmix_strerror.argtypes = [I]
         L.kvmix_last_hip_error.restype = I
         L.kvmix_cache_bytes.restype = I
-        L.kvmix_cache_bytes.argtypes = [P, P, I, I] + [P] * 5
+        L.kvmix_cache_bytes.argtypes = [P, P, I, I, P, P]
         L.kvmix_workspace_bytes.restype = I
         L.kvmix_workspace_bytes.argtypes = [P, I, P]
         L.kvmix_quantize_pack.restype = I
@@ -81,10 +81,10 @@ def _stream():
 
 
 def cache_bytes(shape, cfg, T_cap, W_cap):
-    """-> dict of byte sizes (k_code, k_meta, v_code, v_meta, win)."""
-    out = [C.c_size_t(0) for _ in range(5)]
+    """-> dict of byte sizes: packed (the tile records), win (each of the two window arrays)."""
+    out = [C.c_size_t(0) for _ in range(2)]
     _check(lib().kvmix_cache_bytes(C.byref(shape), C.byref(cfg), T_cap, W_cap, *[C.byref(o) for o in out]), "kvmix_cache_bytes")
-    return dict(zip(("k_code", "k_meta", "v_code", "v_meta", "win"), (o.value for o in out)))
+    return dict(zip(("packed", "win"), (o.value for o in out)))
 
 
 def workspace_bytes(shape, T_max):
@@ -101,13 +101,9 @@ class LayerCache:
         self.shape, self.cfg = shape, cfg
         sz = cache_bytes(shape, cfg, T_cap, W_cap)
         z = lambda n: torch.zeros(max(n, 16), dtype=torch.uint8, device=device)
-        self.k_codes, self.v_codes = z(sz["k_code"]), z(sz["v_code"])
-        self.k_scale, self.k_zero = z(sz["k_meta"]), z(sz["k_meta"])
-        self.v_scale, self.v_zero = z(sz["v_meta"]), z(sz["v_meta"])
+        self.packed = z(sz["packed"])
         self.k_win, self.v_win = z(sz["win"]), z(sz["win"])
-        self.c = _CacheStruct(self.k_codes.data_ptr(), self.k_scale.data_ptr(), self.k_zero.data_ptr(),
-                              self.v_codes.data_ptr(), self.v_scale.data_ptr(), self.v_zero.data_ptr(),
-                              self.k_win.data_ptr(), self.v_win.data_ptr(), T_cap, W_cap, 0, 0, 0)
+        self.c = _CacheStruct(self.packed.data_ptr(), self.k_win.data_ptr(), self.v_win.data_ptr(), T_cap, W_cap, 0, 0, 0)
 
     n_q = property(lambda self: self.c.n_q)
     n_w = property(lambda self: self.c.n_w)
@@ -116,8 +112,7 @@ class LayerCache:
     W_cap = property(lambda self: self.c.W_cap)
 
     def nbytes(self):
-        return sum(t.numel() for t in (self.k_codes, self.v_codes, self.k_scale, self.k_zero, self.v_scale, self.v_zero,
-                                       self.k_win, self.v_win))
+        return sum(t.numel() for t in (self.packed, self.k_win, self.v_win))
 
     def set_window(self, k, v):
         """k, v: fp16 tensors [B][Hkv][n_w][128] (oldest first); plain copies into the ring, start slot 0."""

@@ -44,10 +44,10 @@ int check_cache(const kvmix_layer_cfg* cfg, const kvmix_layer_cache* c, bool nee
   if (!aligned16(c->k_win) || !aligned16(c->v_win)) return KVMIX_ERR_ALIGN;
   if (cfg->k_bits == 16) return c->n_q == 0 ? KVMIX_OK : KVMIX_ERR_BAD_BITS;
   if (need_packed || c->n_q > 0) {
-    if (!c->k_codes || !c->k_scale || !c->k_zero || !c->v_codes || !c->v_scale || !c->v_zero) return KVMIX_ERR_NULL;
-    if (!aligned16(c->k_codes) || !aligned16(c->k_scale) || !aligned16(c->k_zero) || !aligned16(c->v_codes) ||
-        !aligned16(c->v_scale) || !aligned16(c->v_zero))
-      return KVMIX_ERR_ALIGN;
+    if (!c->packed) return KVMIX_ERR_NULL;
+    if (!aligned16(c->packed)) return KVMIX_ERR_ALIGN;
+    // a unit's records are addressed with 32-bit byte offsets
+    if ((long long)(c->T_cap / kTile) * record_words(cfg->k_bits, cfg->v_bits) * 4 > 0x7fffffffLL) return KVMIX_ERR_BAD_SHAPE;
   }
   return KVMIX_OK;
 }
@@ -63,8 +63,7 @@ int max_splits(const kvmix_shape* sh) {
 size_t counters_bytes(int units) { return (((size_t)units * 4 + 255) / 256) * 256; }
 
 void fill_quant_dst(QuantArgs& a, const kvmix_layer_cache* c) {
-  a.k_codes = c->k_codes; a.k_scale = c->k_scale; a.k_zero = c->k_zero;
-  a.v_codes = c->v_codes; a.v_scale = c->v_scale; a.v_zero = c->v_zero;
+  a.packed = c->packed;
   a.tiles_cap = c->T_cap / kTile;
 }
 
@@ -91,16 +90,13 @@ const char* kvmix_strerror(int status) {
 int kvmix_last_hip_error(void) { return g_last_hip_error.load(); }
 
 int kvmix_cache_bytes(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, int T_cap, int W_cap,
-                      size_t* k_code_b, size_t* k_meta_b, size_t* v_code_b, size_t* v_meta_b, size_t* win_b) {
+                      size_t* packed_b, size_t* win_b) {
   const int st = check_shape_cfg(sh, cfg);
   if (st) return st;
   if (T_cap < 0 || T_cap % kTile || W_cap < kTile || W_cap % kTile) return KVMIX_ERR_BAD_SHAPE;
   const size_t units = (size_t)sh->B * sh->Hkv, tiles = (size_t)T_cap / kTile;
   const bool packed = cfg->k_bits != 16;
-  if (k_code_b) *k_code_b = packed ? units * tiles * tile_words(cfg->k_bits) * 4 : 0;
-  if (v_code_b) *v_code_b = packed ? units * tiles * tile_words(cfg->v_bits) * 4 : 0;
-  if (k_meta_b) *k_meta_b = packed ? units * tiles * kD * 2 : 0;
-  if (v_meta_b) *v_meta_b = packed ? units * tiles * kD * 2 : 0;
+  if (packed_b) *packed_b = packed ? units * tiles * record_words(cfg->k_bits, cfg->v_bits) * 4 : 0;
   if (win_b) *win_b = units * (size_t)W_cap * kD * 2;
   return KVMIX_OK;
 }
@@ -206,8 +202,7 @@ int kvmix_decode_attn(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const u
     a.part = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) + counters_bytes(units));
   }
   a.q = q; a.out = out;
-  a.k_codes = c->k_codes; a.k_scale = c->k_scale; a.k_zero = c->k_zero;
-  a.v_codes = c->v_codes; a.v_scale = c->v_scale; a.v_zero = c->v_zero;
+  a.packed = c->packed;
   a.k_win = c->k_win; a.v_win = c->v_win;
   a.tiles_cap = c->T_cap / kTile; a.W_cap = c->W_cap; a.n_tiles = c->n_q / kTile; a.n_w = c->n_w; a.w0 = c->w0;
   a.Hq = sh->Hq; a.Hkv = sh->Hkv; a.n_splits = n_splits;
@@ -227,11 +222,9 @@ int kvmix_dequant(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const kvmix
   st = check_cache(cfg, c, true);
   if (st) return st;
   DequantArgs a{};
-  a.codes = which ? c->v_codes : c->k_codes;
-  a.scale = which ? c->v_scale : c->k_scale;
-  a.zero = which ? c->v_zero : c->k_zero;
+  a.packed = c->packed;
   a.out = out; a.tiles_cap = c->T_cap / kTile; a.n_tiles = c->n_q / kTile;
-  a.bits = which ? cfg->v_bits : cfg->k_bits; a.which = which;
+  a.k_bits = cfg->k_bits; a.v_bits = cfg->v_bits; a.which = which;
   const hipError_t e = launch_dequant(a, sh->B * sh->Hkv, (hipStream_t)stream);
   return e == hipSuccess ? KVMIX_OK : hip_fail(e);
 }

@@ -13,8 +13,8 @@
 // ~22 bits; the up-to-8 query heads of the group use columns 0..7 (hi) and 8..15 (lo).
 // The zero-point sums and the fp16 window are MFMAs on plain fp16 operands.
 //
-// Data movement. Every byte of a tile is loaded from HBM once, by one lane (16 B of codes,
-// 4 B of each scale / zero array per lane), several tiles ahead of its use. The scale-folded
+// Data movement. Every byte of a tile record is loaded from HBM once, by one lane (16 B of
+// metadata and 16 B of every 1 KiB of codes per lane), ahead of its use. The scale-folded
 // B operands are computed cooperatively (each lane two values per head) and redistributed
 // through a wave-private LDS area, so no barrier is needed inside the main loop.
 // Softmax is online, per wave, with a lazily raised reference maximum; waves of a workgroup
@@ -109,9 +109,6 @@ __device__ __forceinline__ u32x4_t buf_load16(rsrc_t r, uint32_t voff, uint32_t 
 __device__ __forceinline__ u32x2_t buf_load8(rsrc_t r, uint32_t voff, uint32_t soff) {
   return __builtin_bit_cast(u32x2_t, __builtin_amdgcn_raw_buffer_load_b64(r, (int)voff, (int)soff, 0));
 }
-__device__ __forceinline__ uint32_t buf_load4(rsrc_t r, uint32_t voff, uint32_t soff) {
-  return (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(r, (int)voff, (int)soff, 0);
-}
 
 // The lane's share of one packed tile as loaded (Raw) and prepared for unpacking (Codes).
 template <int BITS> struct Raw;
@@ -151,23 +148,19 @@ template <> struct Codes<4> {
   __device__ __forceinline__ half8_t lo(int slot) const { return unpack4(wa[slot >> 2], wb[slot >> 2], slot & 3); }
 };
 
-// Buffer resources of one unit's packed arrays (wave-uniform).
-struct UnitBufs { rsrc_t kc, ks, kz, vc, vs, vz; };
-
-// One tile in flight: codes plus the lane's two scales / zero-points of each array.
+// One tile in flight: the lane's 16 bytes of metadata (Key scale pair, Key minimum pair, Value scale
+// pair, Value minimum pair) and its share of the two code sections. The record of a tile is contiguous
+// in memory, so a tile is three to five full-width loads from one stream.
 template <int KB, int VB> struct Stage {
+  u32x4_t meta;
   Raw<KB> kc; Raw<VB> vc;
-  uint32_t ks, kz, vs, vz;
-  // t: tile index inside the unit (wave-uniform)
-  __device__ __forceinline__ void load(const UnitBufs& u, int t, int lane) {
-    const uint32_t l16 = 16u * lane, l8 = 8u * lane, l4 = 4u * lane;
-    const uint32_t ut = (uint32_t)t;
-    kc.load(u.kc, ut * (uint32_t)(tile_words(KB) * 4), l16, l8);
-    ks = buf_load4(u.ks, l4, ut * (uint32_t)(kD * 2));
-    kz = buf_load4(u.kz, l4, ut * (uint32_t)(kD * 2));
-    vc.load(u.vc, ut * (uint32_t)(tile_words(VB) * 4), l16, l8);
-    vs = buf_load4(u.vs, l4, ut * (uint32_t)(kD * 2));
-    vz = buf_load4(u.vz, l4, ut * (uint32_t)(kD * 2));
+  // rec: buffer resource over the unit's records; t: tile index inside the unit (wave-uniform)
+  __device__ __forceinline__ void load(rsrc_t rec, int t, int lane) {
+    const uint32_t l16 = 16u * lane, l8 = 8u * lane;
+    const uint32_t soff = (uint32_t)t * (uint32_t)(record_words(KB, VB) * 4);
+    meta = buf_load16(rec, l16, soff);
+    kc.load(rec, soff + (uint32_t)(kMetaWords * 4), l16, l8);
+    vc.load(rec, soff + (uint32_t)((kMetaWords + tile_words(KB)) * 4), l16, l8);
   }
 };
 
@@ -356,17 +349,8 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
   }
 
   // ---- packed tiles: kDepth tiles in flight per wave, taken from the workgroup's counter
-  UnitBufs up;
-  {
-    const size_t tile_base = (size_t)u * a.tiles_cap;
-    const uint32_t nt = (uint32_t)a.tiles_cap;
-    up.kc = make_rsrc(reinterpret_cast<const char*>(a.k_codes) + tile_base * (tile_words(KB) * 4), nt * (uint32_t)(tile_words(KB) * 4));
-    up.vc = make_rsrc(reinterpret_cast<const char*>(a.v_codes) + tile_base * (tile_words(VB) * 4), nt * (uint32_t)(tile_words(VB) * 4));
-    up.ks = make_rsrc(reinterpret_cast<const char*>(a.k_scale) + tile_base * (kD * 2), nt * (uint32_t)(kD * 2));
-    up.kz = make_rsrc(reinterpret_cast<const char*>(a.k_zero) + tile_base * (kD * 2), nt * (uint32_t)(kD * 2));
-    up.vs = make_rsrc(reinterpret_cast<const char*>(a.v_scale) + tile_base * (kD * 2), nt * (uint32_t)(kD * 2));
-    up.vz = make_rsrc(reinterpret_cast<const char*>(a.v_zero) + tile_base * (kD * 2), nt * (uint32_t)(kD * 2));
-  }
+  constexpr uint32_t kRecBytes = (uint32_t)(record_words(KB, VB) * 4);
+  const rsrc_t up = make_rsrc(reinterpret_cast<const char*>(a.packed) + (size_t)u * a.tiles_cap * kRecBytes, (uint32_t)a.tiles_cap * kRecBytes);
   auto grab = [&]() -> int {
     int it = 0;
     if (lane == 0) it = atomicAdd(&s_next, 1);
@@ -376,7 +360,7 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
   auto process = [&](const Stage<KB, VB>& st, bool live) {
     // -- Key side. Cooperative operand preparation: lane owns channels 2*lane, 2*lane+1.
     {
-      const float s0 = lo_half(st.ks), s1 = hi_half(st.ks);
+      const float s0 = lo_half(st.meta[0]), s1 = hi_half(st.meta[0]);
 #pragma unroll
       for (int hh = 0; hh < G; hh++) {
         uint32_t hi, lo;
@@ -384,7 +368,7 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
         reinterpret_cast<uint32_t*>(&L.bk[hh][0])[lane] = hi;
         reinterpret_cast<uint32_t*>(&L.bk[G + hh][0])[lane] = lo;
       }
-      reinterpret_cast<uint32_t*>(&L.zk[0])[lane] = st.kz;
+      reinterpret_cast<uint32_t*>(&L.zk[0])[lane] = st.meta[1];
     }
     wave_lds_fence();
     float x[8], zt;
@@ -433,7 +417,7 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
     wave_lds_fence();
     {
       const int tp = lane & 15, g = lane >> 4;
-      const float s0 = lo_half(st.vs), s1 = hi_half(st.vs);
+      const float s0 = lo_half(st.meta[2]), s1 = hi_half(st.meta[2]);
 #pragma unroll
       for (int hh = 0; hh < G; hh++) {
         float off = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, off_col), hh));
@@ -452,7 +436,7 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
           reinterpret_cast<uint32_t*>(&L.pb[G + hh][0])[tp] = lo;
         }
       }
-      reinterpret_cast<uint32_t*>(&L.zv[0][0])[lane] = st.vz;
+      reinterpret_cast<uint32_t*>(&L.zv[0][0])[lane] = st.meta[3];
     }
     wave_lds_fence();
     {

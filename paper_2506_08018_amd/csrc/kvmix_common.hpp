@@ -18,6 +18,12 @@ typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
 __host__ __device__ constexpr int tile_words(int bits) { return 128 * bits; }  // 32 x 128 codes
+// A tile record: 256 metadata words, then the Key code section, then the Value code section.
+constexpr int kMetaWords = 256;
+__host__ __device__ constexpr int record_words(int k_bits, int v_bits) { return kMetaWords + tile_words(k_bits) + tile_words(v_bits); }
+// 16-bit index, inside a record, of the metadata halves (f = 0 scale, 1 minimum)
+__host__ __device__ constexpr int key_meta_half(int d, int f) { return 2 * (4 * (d >> 1) + f) + (d & 1); }
+__host__ __device__ constexpr int value_meta_half(int tau, int g, int f) { return 2 * (4 * (16 * g + (tau >> 1)) + 2 + f) + (tau & 1); }
 
 // Position of a code inside its tile (layout statement: include/kvmix.h).
 // (l, j, hh, slot): 16-byte column, word in column, 16-bit half, slot in half.
@@ -57,16 +63,15 @@ struct QuantArgs {
   const uint16_t* k; const uint16_t* v;
   int64_t k_tok, k_unit_b, k_unit_h;            // Key input: channel stride 1
   int64_t v_tok, v_chan, v_unit_b, v_unit_h;    // Value input: channel stride 1 or token stride 1
-  uint32_t* k_codes; uint16_t* k_scale; uint16_t* k_zero;
-  uint32_t* v_codes; uint16_t* v_scale; uint16_t* v_zero;
+  uint32_t* packed;
   int tiles_cap;   // tiles per unit in the packed cache
   int tile0;       // first destination tile
   int Hkv;
 };
 
 struct DequantArgs {
-  const uint32_t* codes; const uint16_t* scale; const uint16_t* zero;
-  float* out; int tiles_cap; int n_tiles; int bits; int which;
+  const uint32_t* packed;
+  float* out; int tiles_cap; int n_tiles; int k_bits; int v_bits; int which;
 };
 
 struct AppendArgs {
@@ -77,8 +82,7 @@ struct AppendArgs {
 
 struct AttnArgs {
   const uint16_t* q; uint16_t* out;
-  const uint32_t* k_codes; const uint16_t* k_scale; const uint16_t* k_zero;
-  const uint32_t* v_codes; const uint16_t* v_scale; const uint16_t* v_zero;
+  const uint32_t* packed;
   const uint16_t* k_win; const uint16_t* v_win;
   float* part;            // split partials: [units][n_splits][G][kD + 2]
   uint32_t* counters;     // [units] arrival counters (zero before and after every call)

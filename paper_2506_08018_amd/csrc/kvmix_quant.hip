@@ -135,7 +135,8 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(QuantArgs a) {
   }
   __syncthreads();
 
-  const size_t tile = (size_t)u * a.tiles_cap + (size_t)(a.tile0 + tile_in);
+  uint32_t* rec = a.packed + ((size_t)u * a.tiles_cap + (size_t)(a.tile0 + tile_in)) * record_words(KB, VB);
+  uint16_t* meta = reinterpret_cast<uint16_t*>(rec);
   float x[32];
   uint8_t code[32];
   uint16_t sh, zh;
@@ -146,8 +147,8 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(QuantArgs a) {
     quantize_group<KB>(x, code, sh, zh);
 #pragma unroll
     for (int t = 0; t < 32; t++) cs[0][t * kD + d] = code[t];
-    a.k_scale[tile * kD + d] = sh;
-    a.k_zero[tile * kD + d] = zh;
+    meta[key_meta_half(d, 0)] = sh;
+    meta[key_meta_half(d, 1)] = zh;
   } else {
     const int tau = (tid - 128) & 31, g = (tid - 128) >> 5;  // Value group: token tau, channels 32g..32g+31
 #pragma unroll
@@ -163,39 +164,40 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(QuantArgs a) {
       uint32_t w = (uint32_t)code[4 * c] | ((uint32_t)code[4 * c + 1] << 8) | ((uint32_t)code[4 * c + 2] << 16) | ((uint32_t)code[4 * c + 3] << 24);
       *reinterpret_cast<uint32_t*>(&cs[1][tau * kD + 32 * g + 4 * c]) = w;
     }
-    a.v_scale[tile * kD + g * kTile + tau] = sh;   // [tile][g][tau]
-    a.v_zero[tile * kD + g * kTile + tau] = zh;
+    meta[value_meta_half(tau, g, 0)] = sh;
+    meta[value_meta_half(tau, g, 1)] = zh;
   }
   __syncthreads();
 
-  pack_tile<KB, false>(cs[0], a.k_codes + tile * tile_words(KB), tid, 256);
-  pack_tile<VB, true>(cs[1], a.v_codes + tile * tile_words(VB), tid, 256);
+  pack_tile<KB, false>(cs[0], rec + kMetaWords, tid, 256);
+  pack_tile<VB, true>(cs[1], rec + kMetaWords + tile_words(KB), tid, 256);
 }
 
 // x = code * s_i + min, evaluated in fp32 (multiply, then add).
 __global__ __launch_bounds__(256) void dequant_kernel(DequantArgs a) {
   const int u = blockIdx.y, tile_i = blockIdx.x;
-  const size_t tile = (size_t)u * a.tiles_cap + tile_i;
-  const uint32_t* words = a.codes + tile * tile_words(a.bits);
+  const uint32_t* rec = a.packed + ((size_t)u * a.tiles_cap + tile_i) * record_words(a.k_bits, a.v_bits);
+  const uint16_t* meta = reinterpret_cast<const uint16_t*>(rec);
+  const int bits = a.which ? a.v_bits : a.k_bits;
+  const uint32_t* words = rec + kMetaWords + (a.which ? tile_words(a.k_bits) : 0);
   for (int e = threadIdx.x; e < kTile * kD; e += blockDim.x) {
     const int tau = e / kD, d = e % kD;
-    int l, j, hh, slot, gi;
-    size_t mi;
+    int l, j, hh, slot, gi, ms, mz;
     if (a.which == 0) {
       const int ks = d / 32, kq = (d % 32) / 8, m = (tau % 8) / 4, i = 4 * (tau / 8) + tau % 4;
       l = 16 * kq + i; j = (d % 8) / 2; hh = d % 2; slot = ks + 4 * m;
-      mi = tile * kD + d; gi = tau;
+      ms = key_meta_half(d, 0); mz = key_meta_half(d, 1); gi = tau;
     } else {
       l = 16 * (tau / 8) + d % 16; j = (tau % 8) / 2; hh = tau % 2; slot = d / 16;
-      mi = tile * kD + (size_t)(d / 32) * kTile + tau; gi = d % 32;
+      ms = value_meta_half(tau, d / 32, 0); mz = value_meta_half(tau, d / 32, 1); gi = d % 32;
     }
-    const CodePos p = pos_from_slots(a.bits, l, j, hh, slot);
+    const CodePos p = pos_from_slots(bits, l, j, hh, slot);
     int code;
-    if (a.bits == 3) code = ((words[p.word] >> p.bit) & 3u) + 4 * ((words[p.hword] >> p.hbit) & 1u);
-    else code = (words[p.word] >> p.bit) & ((1u << a.bits) - 1u);
-    const float s = (float)__builtin_bit_cast(half_t, a.scale[mi]);
-    const float mn = (float)__builtin_bit_cast(half_t, a.zero[mi]);
-    const float si = (a.bits == 3 && (gi == 10 || gi == 21)) ? (s * 7.0f) / 3.0f : s;
+    if (bits == 3) code = ((words[p.word] >> p.bit) & 3u) + 4 * ((words[p.hword] >> p.hbit) & 1u);
+    else code = (words[p.word] >> p.bit) & ((1u << bits) - 1u);
+    const float s = (float)__builtin_bit_cast(half_t, meta[ms]);
+    const float mn = (float)__builtin_bit_cast(half_t, meta[mz]);
+    const float si = (bits == 3 && (gi == 10 || gi == 21)) ? (s * 7.0f) / 3.0f : s;
     const float prod = (float)code * si;
     a.out[((size_t)u * a.n_tiles + tile_i) * kTile * kD + e] = prod + mn;
   }

@@ -50,18 +50,25 @@ def make_pair(B, Hq, Hkv, T, W, kb, vb, seed=0, layer=0, T_cap=None, W_cap=None,
     return q, k, v, rc, gc, shape, cfg
 
 
+def gpu_fields(gc, rc):
+    """The GPU cache's record buffer cut into fields with the layout statement's decoder (on the host)."""
+    from oracle.kvmix_ref import split_records
+    want = rc.packed
+    got = bits_of(gc.packed, np.uint32)[: want.size].reshape(want.shape)
+    return got, split_records(got, rc.kb, rc.vb)
+
+
 def assert_cache_equal(rc, gc, n_tiles=None):
-    """Bit-exact comparison of codes, scales and zero-points of the packed tiles."""
+    """Bit-exact comparison of the tile records (codes, scales and minima) of the packed tiles."""
     nt = rc.n_q // 32 if n_tiles is None else n_tiles
-    units = rc.units
-    for name, dt in (("k_codes", np.uint32), ("v_codes", np.uint32), ("k_scale", np.uint16), ("k_zero", np.uint16),
-                     ("v_scale", np.uint16), ("v_zero", np.uint16)):
-        want = getattr(rc, name)
-        got = bits_of(getattr(gc, name), dt)[: want.size].reshape(want.shape)
-        assert units == want.shape[0]
-        if not np.array_equal(got[:, :nt], want[:, :nt]):
-            bad = np.argwhere(got[:, :nt] != want[:, :nt])
-            raise AssertionError(f"{name}: {len(bad)} mismatching entries, first at {bad[0]}: got {got[:, :nt][tuple(bad[0])]:#x} want {want[:, :nt][tuple(bad[0])]:#x}")
+    got_packed, got = gpu_fields(gc, rc)
+    want = rc.fields()
+    for name in ("k_codes", "v_codes", "k_scale", "k_zero", "v_scale", "v_zero"):   # field by field first: better messages
+        g, w = got[name][:, :nt], want[name][:, :nt]
+        if not np.array_equal(g, w):
+            bad = np.argwhere(g != w)
+            raise AssertionError(f"{name}: {len(bad)} mismatching entries, first at {bad[0]}: got {g[tuple(bad[0])]:#x} want {w[tuple(bad[0])]:#x}")
+    assert np.array_equal(got_packed[:, :nt], rc.packed[:, :nt]), "tile records differ outside the decoded fields"
 
 
 TIGHT_ABS = 1e-4  # accumulation noise floor (fp32 sums, matrix-core product truncation) on top of one fp16 spacing

@@ -37,8 +37,7 @@ def test_full_size_sampled_units(name, n_sample):
         assert not ws[: 4 * shape.units].any()
         units = rng.choice(B * Hkv, min(n_sample, B * Hkv), replace=False)
         tiles = n_q // 32
-        kcodes = gc.k_codes.view(torch.int32).view(B * Hkv, tiles, -1)
-        vcodes = gc.v_codes.view(torch.int32).view(B * Hkv, tiles, -1)
+        records = gc.packed.view(torch.int32).view(B * Hkv, tiles, -1)
         for u in units:
             b, j = divmod(int(u), Hkv)
             ku, vu = t16(k[b, j]).reshape(1, 1, T, 128), t16(v[b, j]).reshape(1, 1, T, 128)
@@ -46,8 +45,7 @@ def test_full_size_sampled_units(name, n_sample):
             rc = RefCache(1, G, 1, kb, vb, W, n_q, W + 32)
             assert rc.quantize_pack(ku[:, :, :n_q], vu[:, :, :n_q]) == 0
             rc.set_window(ku[:, :, n_q:], vu[:, :, n_q:])
-            assert np.array_equal(kcodes[u].cpu().numpy().view(np.uint32), rc.k_codes[0]), f"K codes of unit {u}"
-            assert np.array_equal(vcodes[u].cpu().numpy().view(np.uint32), rc.v_codes[0]), f"V codes of unit {u}"
+            assert np.array_equal(records[u].cpu().numpy().view(np.uint32), rc.packed[0]), f"tile records of unit {u}"
             st, want = rc.decode_attn(qu)
             assert st == 0
             assert_attn_close(t16(out[b, j * G:(j + 1) * G]).reshape(1, G, 128), want, f"{name} unit {u} bits {kb}/{vb}", tight=True)

@@ -102,4 +102,4 @@ def test_error_returns_launch_nothing():
     with pytest.raises(kv.KVMixError) as e:
         kv.quantize_pack(kv.Shape(1, 2, 2, 128, 64), cfg, k[:, :, :32], k[:, :, :32], gc)
     assert e.value.status == -3
-    assert gc.n_q == 0 and not bits_of(gc.k_codes, np.uint32).any()
+    assert gc.n_q == 0 and not bits_of(gc.packed, np.uint32).any()

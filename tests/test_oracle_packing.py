@@ -64,3 +64,38 @@ def test_three_bit_unused_bits_zero_after_quantize(ref):
     vc = ref.unpack_tile(1, 3, c.v_codes[0, 0])
     assert kc[[10, 21], :].max() <= 3 and kc.max() == 7     # Key groups run along tokens
     assert vc[:, [10, 21, 42, 53, 74, 85, 106, 117]].max() <= 3 and vc.max() == 7  # Value groups along channels
+
+
+@pytest.mark.parametrize("kb,vb", [(2, 2), (3, 4), (4, 3)])
+def test_tile_record_places_every_group(ref, kb, vb):
+    """The tile record written by the cache-level quantize-pack holds, at the places the layout statement
+    names (metadata word 4l+f, code sections after the 256 metadata words), exactly what the group
+    quantizer returns for each Key group (one channel, 32 tokens) and Value group (one token, 32 channels)."""
+    from oracle.kvmix_ref import RefCache, record_words
+    rng = np.random.default_rng(kb * 10 + vb)
+    k = (rng.standard_normal((1, 2, 64, 128)) * rng.uniform(0.2, 5.0, (1, 2, 1, 128))).astype(np.float16)
+    v = (rng.standard_normal((1, 2, 64, 128)) * rng.uniform(0.2, 5.0, (1, 2, 64, 1))).astype(np.float16)
+    c = RefCache(1, 2, 2, kb, vb, 32, 96, 64)
+    assert c.quantize_pack(k.view(np.uint16), v.view(np.uint16)) == 0
+    assert record_words(kb, vb) == 256 + 128 * kb + 128 * vb and c.packed.shape == (2, 3, record_words(kb, vb))
+    assert not c.packed[:, 2].any()                       # the unused third tile stays zero
+    for u in range(2):
+        for t in range(2):
+            rec = c.packed[u, t]
+            meta16 = rec[:256].view(np.uint16)            # little-endian: low half first
+            kcodes = ref.unpack_tile(0, kb, rec[256:256 + 128 * kb])
+            vcodes = ref.unpack_tile(1, vb, rec[256 + 128 * kb:])
+            for d in range(128):
+                codes, s, z = ref.quantize_group(k[0, u, 32 * t:32 * t + 32, d].view(np.uint16), kb)
+                l = d // 2
+                assert meta16[2 * (4 * l + 0) + d % 2] == s and meta16[2 * (4 * l + 1) + d % 2] == z
+                assert np.array_equal(kcodes[:, d], codes)
+            for tau in range(32):
+                for g in range(4):
+                    codes, s, z = ref.quantize_group(v[0, u, 32 * t + tau, 32 * g:32 * g + 32].view(np.uint16), vb)
+                    l = 16 * g + tau // 2
+                    assert meta16[2 * (4 * l + 2) + tau % 2] == s and meta16[2 * (4 * l + 3) + tau % 2] == z
+                    assert np.array_equal(vcodes[tau, 32 * g:32 * g + 32], codes)
+    f = c.fields()                                         # the test helper agrees with the same statement
+    assert f["k_scale"][1, 0, 77] == c.packed[1, 0, 4 * 38].item() >> 16
+    assert f["v_zero"][0, 1, 2, 9] == c.packed[0, 1, 4 * (32 + 4) + 3].item() >> 16
