@@ -18,8 +18,9 @@
 // B operands are computed cooperatively (each lane two values per head) and redistributed
 // through a wave-private LDS area, so no barrier is needed inside the main loop.
 // Softmax is online, per wave, with a lazily raised reference maximum; waves of a workgroup
-// take tiles from a shared counter and merge through LDS; splits of one unit merge through a
-// workspace, the last arriving workgroup writes the output.
+// take tiles from a shared counter and merge through LDS (without a barrier when the unit is not
+// split: the last wave to deliver combines); splits of one unit merge through a workspace, the
+// last arriving workgroup writes the output.
 #include "kvmix_common.hpp"
 
 namespace kvmix {
@@ -44,6 +45,33 @@ __device__ __forceinline__ float ror8(float v) {
   return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x128, 0xf, 0xf, false));
 }
 __device__ __forceinline__ half8_t as_half8(u32x4_t v) { return __builtin_bit_cast(half8_t, v); }
+template <int CTRL, int ROW_MASK = 0xf>
+__device__ __forceinline__ float dpp_f(float v) {   // lanes without a source (or outside ROW_MASK) read 0
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xf, false));
+}
+// sum over the 16 lanes of each row; every lane of the row gets it
+__device__ __forceinline__ float row_sum(float v) {
+  v += dpp_f<0xB1>(v);    // quad_perm [1,0,3,2]
+  v += dpp_f<0x4E>(v);    // quad_perm [2,3,0,1]
+  v += dpp_f<0x141>(v);   // row_half_mirror
+  v += dpp_f<0x140>(v);   // row_mirror
+  return v;
+}
+// sum over the 64 lanes of the wave as a wave-uniform value
+__device__ __forceinline__ float wave_sum(float v) {
+  v = row_sum(v);
+  v += dpp_f<0x142, 0xA>(v);   // row_bcast:15 -> rows 1 and 3 add the sum of the row before
+  v += dpp_f<0x143, 0xC>(v);   // row_bcast:31 -> rows 2 and 3 add the sum of rows 0..1
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
+}
+__device__ __forceinline__ float wave_max(float v) {   // rare path: plain butterflies
+  v = fmaxf(v, __shfl_xor(v, 1)); v = fmaxf(v, __shfl_xor(v, 2)); v = fmaxf(v, __shfl_xor(v, 4));
+  v = fmaxf(v, __shfl_xor(v, 8)); v = fmaxf(v, __shfl_xor(v, 16)); v = fmaxf(v, __shfl_xor(v, 32));
+  return v;
+}
+__device__ __forceinline__ float uniform_lane(float v, int l) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), l));
+}
 // orders the wave's own LDS writes before its following LDS reads (LDS executes a wave's
 // operations in order; this only pins the compiler)
 __device__ __forceinline__ void wave_lds_fence() {
@@ -196,23 +224,20 @@ template <int G> struct __attribute__((aligned(16))) WaveLds {
   uint16_t zv[4][kTile];                   // Value zero-points [channel block][token]
 };
 
-template <int G> struct MergeLds {        // per-wave results, reuses the exchange memory after the main loop
+template <int G> struct MergeLds {        // per-wave results (its own memory: a wave that is done never waits for the others)
   float o[waves_for(G)][G][kD];
   float m[waves_for(G)][G];
   float l[waves_for(G)][G];
 };
 
-template <int G> constexpr size_t smem_bytes() {
-  return sizeof(WaveLds<G>) * waves_for(G) > sizeof(MergeLds<G>) ? sizeof(WaveLds<G>) * waves_for(G) : sizeof(MergeLds<G>);
-}
-
 template <int KB, int VB, int G>
 __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnArgs a) {
   constexpr int kWaves = waves_for(G);
   constexpr int kThreads = kWaves * kWave;
-  __shared__ __attribute__((aligned(16))) char smem[smem_bytes<G>()];
-  __shared__ int s_next;
-  __shared__ int s_last;
+  __shared__ WaveLds<G> s_wave[kWaves];
+  __shared__ MergeLds<G> R;
+  __shared__ int s_next;   // next unclaimed packed tile of this workgroup
+  __shared__ int s_done;   // waves that have delivered their result
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int col = lane & 15, kq = lane >> 4;         // MFMA column / row index, k-quarter
@@ -221,8 +246,7 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
   const bool col_valid = h < G;
   const int sp = blockIdx.x, u = blockIdx.y;
   const int b = u / a.Hkv, jh = u % a.Hkv;
-  WaveLds<G>& L = reinterpret_cast<WaveLds<G>*>(smem)[wave];
-  MergeLds<G>& R = *reinterpret_cast<MergeLds<G>*>(smem);
+  WaveLds<G>& L = s_wave[wave];
   const int row = col_valid ? (lo_part ? G + h : h) : WaveLds<G>::kRows;   // operand row of this lane's column
 
   // work items of this split: window tiles first, then packed tiles
@@ -234,20 +258,14 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
   const int win_end = item_end < n_wt ? item_end : n_wt;
   const int p_begin = (item_begin > n_wt ? item_begin : n_wt) - n_wt;
   const int p_end = (item_end > n_wt ? item_end : n_wt) - n_wt;
-  if (tid == 0) s_next = p_begin;
 
-  // zero the exchange area: rows of unused columns stay zero for the whole kernel
+  // ---- everything that has to come from HBM first is requested before anything else is done:
+  // the query, then the wave's first window tile or, for the waves without one, its first packed tiles.
+  // Packed tiles are claimed from a workgroup counter; the first claims are static (wave order).
+  const uint16_t* qbase = a.q + ((size_t)b * a.Hq + (size_t)jh * G) * kD;
+  half8_t qB[4];       // plain q as B operand: hi columns hold head h, everything else zero
+  uint32_t qraw[G];    // q of channels (2*lane, 2*lane+1) of every head
   {
-    u32x4_t* z = reinterpret_cast<u32x4_t*>(&L);
-    for (int i = lane; i < (int)(sizeof(WaveLds<G>) / 16); i += kWave) z[i] = u32x4_t{0, 0, 0, 0};
-  }
-  __syncthreads();
-
-  // query operands
-  half8_t qB[4];      // plain q as B operand: hi columns hold head h, everything else zero
-  float qc[G][2];     // q of channels (2*lane, 2*lane+1), prescaled by 2^-field_pos of the lane's channel block
-  {
-    const uint16_t* qbase = a.q + ((size_t)b * a.Hq + (size_t)jh * G) * kD;
     const half8_t zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
     for (int ks = 0; ks < 4; ks++) {
@@ -255,12 +273,71 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
       if (col_valid && !lo_part) v = *reinterpret_cast<const half8_t*>(qbase + (size_t)h * kD + 32 * ks + 8 * kq);
       qB[ks] = v;
     }
+#pragma unroll
+    for (int hh = 0; hh < G; hh++) qraw[hh] = reinterpret_cast<const uint32_t*>(qbase + (size_t)hh * kD)[lane];
+  }
+
+  constexpr uint32_t kRecBytes = (uint32_t)(record_words(KB, VB) * 4);
+  const rsrc_t up = make_rsrc(reinterpret_cast<const char*>(a.packed) + (size_t)u * a.tiles_cap * kRecBytes, (uint32_t)a.tiles_cap * kRecBytes);
+  const int n_win = win_end - win_begin;
+  const int n_early = n_win < kWaves ? kWaves - n_win : 0;      // waves n_win .. kWaves-1 start on packed tiles
+  const bool has_packed = p_end > p_begin;
+  const bool early = has_packed && wave >= n_win;
+  Stage<KB, VB> st[kDepth];
+  int it[kDepth];
+  // Past the end a wave re-reads the last tile (cache hit) and skips its work: the load stream and the
+  // loop body stay uniform, which keeps the outstanding-load accounting exact.
+  if (early) {
+#pragma unroll
+    for (int s = 0; s < kDepth; s++) {
+      it[s] = p_begin + s * n_early + (wave - n_win);
+      st[s].load(up, it[s] < p_end ? it[s] : p_end - 1, lane);
+    }
+  }
+
+  // window tile wi of the ring: registers of the two MFMA A operands (Keys: rows = tokens, Values: rows = channels)
+  struct WinTile { half8_t Ak[2][4], Av[8]; };
+  auto win_first = [&](int wi) { return (wi * kTile - a.w0 + a.W_cap) % a.W_cap; };   // ring rank of the tile's first slot
+  auto win_load = [&](int wi, WinTile& w) {
+    const int slot0 = wi * kTile;
+    const uint16_t* kw = a.k_win + ((size_t)u * a.W_cap + slot0) * kD;
+    const uint16_t* vw = a.v_win + (size_t)u * kD * a.W_cap + slot0 + 8 * kq;
+#pragma unroll
+    for (int m = 0; m < 2; m++) {
+      const int tau = 8 * (col >> 2) + 4 * m + (col & 3);   // row `col` of M-tile m
+#pragma unroll
+      for (int ks = 0; ks < 4; ks++) w.Ak[m][ks] = *reinterpret_cast<const half8_t*>(kw + (size_t)tau * kD + 32 * ks + 8 * kq);
+    }
+#pragma unroll
+    for (int m = 0; m < 4; m++) w.Av[m] = *reinterpret_cast<const half8_t*>(vw + (size_t)(16 * m + col) * a.W_cap);
+  };
+  // second half of the Value rows: requested once the Key rows have been consumed (fewer registers in flight)
+  auto win_load_rest = [&](int wi, WinTile& w) {
+    const uint16_t* vw = a.v_win + (size_t)u * kD * a.W_cap + wi * kTile + 8 * kq;
+#pragma unroll
+    for (int m = 4; m < 8; m++) w.Av[m] = *reinterpret_cast<const half8_t*>(vw + (size_t)(16 * m + col) * a.W_cap);
+  };
+  WinTile wt;
+  int wi = win_begin + wave;
+  // tiles wholly outside the n_w valid tokens are skipped (w0 and tiles are 32-aligned)
+  while (wi < win_end && win_first(wi) >= a.n_w) wi += kWaves;
+  if (wi < win_end) win_load(wi, wt);
+
+  if (tid == 0) { s_next = p_begin + kDepth * n_early; s_done = 0; }
+  // zero the wave's exchange area: rows of unused columns stay zero for the whole kernel
+  {
+    u32x4_t* z = reinterpret_cast<u32x4_t*>(&L);
+    for (int i = lane; i < (int)(sizeof(WaveLds<G>) / 16); i += kWave) z[i] = u32x4_t{0, 0, 0, 0};
+  }
+  __syncthreads();   // the only workgroup barrier before the results are merged: the counters are set
+
+  float qc[G][2];     // q prescaled by 2^-field_pos of the lane's channel block
+  {
     const float pre = __builtin_ldexpf(1.0f, -field_pos<KB>(lane >> 4));
 #pragma unroll
     for (int hh = 0; hh < G; hh++) {
-      const uint32_t v = reinterpret_cast<const uint32_t*>(qbase + (size_t)hh * kD)[lane];
-      qc[hh][0] = lo_half(v) * pre;
-      qc[hh][1] = hi_half(v) * pre;
+      qc[hh][0] = lo_half(qraw[hh]) * pre;
+      qc[hh][1] = hi_half(qraw[hh]) * pre;
     }
   }
 
@@ -299,27 +376,26 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
     return fmaxf(mx, s[7]);
   };
 
-  // ---- fp16 window tiles (few): taken round-robin by the waves before the packed stream
-  for (int wi = win_begin + wave; wi < win_end; wi += kWaves) {
-    const int slot0 = wi * kTile;
-    const int first = (slot0 - a.w0 + a.W_cap) % a.W_cap;   // ring rank of the tile's first slot
-    if (first >= a.n_w) continue;                            // w0 and tiles are 32-aligned
-    const uint16_t* kw = a.k_win + ((size_t)u * a.W_cap + slot0) * kD;
-    const uint16_t* vw = a.v_win + (size_t)u * kD * a.W_cap + slot0 + 8 * kq;
-    half8_t Ak[2][4], Av[8];
-#pragma unroll
-    for (int m = 0; m < 2; m++) {
-      const int tau = 8 * (col >> 2) + 4 * m + (col & 3);   // row `col` of M-tile m
-#pragma unroll
-      for (int ks = 0; ks < 4; ks++) Ak[m][ks] = *reinterpret_cast<const half8_t*>(kw + (size_t)tau * kD + 32 * ks + 8 * kq);
-    }
-#pragma unroll
-    for (int m = 0; m < 8; m++) Av[m] = *reinterpret_cast<const half8_t*>(vw + (size_t)(16 * m + col) * a.W_cap);
+  auto grab = [&]() -> int {
+    int it = 0;
+    if (lane == 0) it = atomicAdd(&s_next, 1);
+    return __builtin_amdgcn_readfirstlane(it);
+  };
+
+  // ---- fp16 window tiles (few): taken round-robin by the waves before the packed stream.
+  // A wave that started on packed tiles has no window tile; the nesting keeps its tile registers
+  // out of the live ranges in here.
+  if (!early) {
+  while (wi < win_end) {
+    const int first = win_first(wi);
+    const half8_t (&Ak)[2][4] = wt.Ak;
+    const half8_t (&Av)[8] = wt.Av;
     float4_t S[2] = {float4_t{0, 0, 0, 0}, float4_t{0, 0, 0, 0}};
 #pragma unroll
     for (int m = 0; m < 2; m++)
 #pragma unroll
       for (int ks = 0; ks < 4; ks++) S[m] = mfma16(Ak[m][ks], qB[ks], S[m]);
+    win_load_rest(wi, wt);
     float x[8], p[8];
 #pragma unroll
     for (int m = 0; m < 2; m++)
@@ -346,18 +422,142 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
       }
       acc[m] += t * __builtin_ldexpf(1.0f, field_pos<VB>(m & 3) - 24);
     }
+    wi += kWaves;
+    while (wi < win_end && win_first(wi) >= a.n_w) wi += kWaves;
+    if (wi < win_end) win_load(wi, wt);
+  }
+  if (has_packed) {   // claim the first packed tiles now
+#pragma unroll
+    for (int s = 0; s < kDepth; s++) {
+      it[s] = grab();
+      st[s].load(up, it[s] < p_end ? it[s] : p_end - 1, lane);
+    }
+  }
   }
 
-  // ---- packed tiles: kDepth tiles in flight per wave, taken from the workgroup's counter
-  constexpr uint32_t kRecBytes = (uint32_t)(record_words(KB, VB) * 4);
-  const rsrc_t up = make_rsrc(reinterpret_cast<const char*>(a.packed) + (size_t)u * a.tiles_cap * kRecBytes, (uint32_t)a.tiles_cap * kRecBytes);
-  auto grab = [&]() -> int {
-    int it = 0;
-    if (lane == 0) it = atomicAdd(&s_next, 1);
-    return __builtin_amdgcn_readfirstlane(it);
+  // ---- small query groups (G <= 2): the matrix core's columns are nearly empty, so the per-tile extras
+  // (Key zero-point term, Value zero-point term, sum of numerators) are cheaper on the vector unit:
+  // a packed dot product plus a wave reduction, and per-lane running sums reduced once at the end.
+  constexpr bool kSmall = G <= 2;
+  float lwin = 0.0f;            // window tiles' sum of numerators of the lane's column (hi + lo)
+  float lacc[G], zacc[G];       // running sum of numerators / of numerator * Value minimum over the lane's tokens
+  float mref_u[G];              // reference of head hh, the same value in every lane
+  if constexpr (kSmall) {
+    lwin = __shfl(accZ[0], 16 + col);
+    lwin += ror8(lwin);
+#pragma unroll
+    for (int hh = 0; hh < G; hh++) {
+      lacc[hh] = 0.0f; zacc[hh] = 0.0f;
+      mref_u[hh] = uniform_lane(mref, hh);
+    }
+  }
+  const float inv_c_code = 1.0f / c_code;
+
+  auto process_small = [&](const Stage<KB, VB>& st) {
+    // -- Key side. Lane owns channels 2*lane, 2*lane+1: scale-folded query to LDS, zero-point term by dot product
+    float zt[G];
+    {
+      const float s0 = lo_half(st.meta[0]), s1 = hi_half(st.meta[0]);
+      const uint32_t kz_pair = st.meta[1];   // a copy: a bit cast applied to the vector element itself reads element 0
+#pragma unroll
+      for (int hh = 0; hh < G; hh++) {
+        uint32_t hi, lo;
+        split_pair(qc[hh][0] * s0, qc[hh][1] * s1, hi, lo);
+        reinterpret_cast<uint32_t*>(&L.bk[hh][0])[lane] = hi;
+        reinterpret_cast<uint32_t*>(&L.bk[G + hh][0])[lane] = lo;
+        const float zp = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, qraw[hh]), __builtin_bit_cast(half2_t, kz_pair), 0.0f, false);
+        zt[hh] = wave_sum(zp) * c_plain;
+      }
+    }
+    wave_lds_fence();
+    {
+      const Codes<KB> kc(st.kc);
+      half8_t Bk[4];
+#pragma unroll
+      for (int ks = 0; ks < 4; ks++) Bk[ks] = *reinterpret_cast<const half8_t*>(&L.bk[row][32 * ks + 8 * kq]);
+      float4_t S[2] = {float4_t{0, 0, 0, 0}, float4_t{0, 0, 0, 0}};
+#pragma unroll
+      for (int m = 0; m < 2; m++)
+#pragma unroll
+        for (int ks = 0; ks < 4; ks++) {
+          S[m] = mfma16(kc.lo(ks + 4 * m), Bk[ks], S[m]);
+          if constexpr (KB == 3) S[m] = mfma16(kc.hi(ks + 4 * m), Bk[ks], S[m]);
+        }
+      if constexpr (KB == 3) {   // tokens 10 and 21 of the group step by s*7/3
+        if (kq == 1) S[0][2] *= (7.0f / 3.0f);
+        if (kq == 2) S[1][1] *= (7.0f / 3.0f);
+      }
+      if (col_valid) {
+        *reinterpret_cast<float4_t*>(&L.s[row][8 * kq]) = S[0];
+        *reinterpret_cast<float4_t*>(&L.s[row][8 * kq + 4]) = S[1];
+      }
+    }
+    wave_lds_fence();
+    // -- Value side. Lane (tp, g) owns tokens (2*tp, 2*tp+1) of channel block g.
+    {
+      const int tp = lane & 15, g = lane >> 4;
+      const float s0 = lo_half(st.meta[2]), s1 = hi_half(st.meta[2]);
+      const float z0 = lo_half(st.meta[3]), z1 = hi_half(st.meta[3]);
+      float sum0[G], sum1[G];
+      bool over = false;
+#pragma unroll
+      for (int hh = 0; hh < G; hh++) {
+        const float2_t sh = *reinterpret_cast<const float2_t*>(&L.s[hh][2 * tp]);
+        const float2_t sl = *reinterpret_cast<const float2_t*>(&L.s[G + hh][2 * tp]);
+        sum0[hh] = sh[0] + sl[0];
+        sum1[hh] = sh[1] + sl[1];
+        // score = sum * c_code + zt; it exceeds the reference iff sum > (reference - zt) / c_code
+        over |= fmaxf(sum0[hh], sum1[hh]) > (mref_u[hh] - zt[hh]) * inv_c_code;
+      }
+      if (__any(over)) {   // rare: raise the reference of the heads that need it and rescale what was accumulated
+#pragma unroll
+        for (int hh = 0; hh < G; hh++) {
+          const float mx = wave_max(fmaxf(sum0[hh], sum1[hh])) * c_code + zt[hh];
+          if (mx > mref_u[hh]) {          // wave-uniform
+            const float mnew = mx + kRefMargin;
+            const float f = fast_exp2(mref_u[hh] - mnew);      // 0 for the first tile (reference -inf)
+            mref_u[hh] = mnew;
+            lacc[hh] *= f; zacc[hh] *= f;
+            if (h == hh) {                // the lanes of this head's columns
+              mref = mnew;
+              lwin *= f;
+#pragma unroll
+              for (int m = 0; m < 8; m++) acc[m] *= f;
+            }
+          }
+        }
+      }
+#pragma unroll
+      for (int hh = 0; hh < G; hh++) {
+        const float off = zt[hh] - mref_u[hh];
+        const float p0 = fast_exp2(sum0[hh] * c_code + off);
+        const float p1 = fast_exp2(sum1[hh] * c_code + off);
+        lacc[hh] += p0 + p1;
+        zacc[hh] += p0 * z0 + p1 * z1;
+        uint32_t hi, lo;
+        split_pair(p0 * s0, p1 * s1, hi, lo);
+        reinterpret_cast<uint32_t*>(&L.bv[g][hh][0])[tp] = hi;
+        reinterpret_cast<uint32_t*>(&L.bv[g][G + hh][0])[tp] = lo;
+      }
+    }
+    wave_lds_fence();
+    {
+      const Codes<VB> vc(st.vc);
+      half8_t Bv[4];
+#pragma unroll
+      for (int g = 0; g < 4; g++) Bv[g] = *reinterpret_cast<const half8_t*>(&L.bv[g][row][8 * kq]);
+#pragma unroll
+      for (int m = 0; m < 8; m++) {
+        acc[m] = mfma16(vc.lo(m), Bv[m >> 1], acc[m]);
+        if constexpr (VB == 3) acc[m] = mfma16(vc.hi(m), Bv[m >> 1], acc[m]);
+      }
+    }
+    wave_lds_fence();   // the next tile's operand writes come after these reads
   };
 
-  auto process = [&](const Stage<KB, VB>& st, bool live) {
+  // ---- packed tiles: kDepth tiles in flight per wave, taken from the workgroup's counter
+
+  auto process_large = [&](const Stage<KB, VB>& st) {
     // -- Key side. Cooperative operand preparation: lane owns channels 2*lane, 2*lane+1.
     {
       const float s0 = lo_half(st.meta[0]), s1 = hi_half(st.meta[0]);
@@ -405,7 +605,7 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
     float mx = max8(x) * c_code + zt;
     const float mx_partner = ror8(mx);        // cross-lane read outside any divergent branch: all lanes must take part
     mx = lo_part ? mx_partner : mx;
-    raise_reference(live ? mx : -INFINITY);
+    raise_reference(mx);
     const float off_col = zt - mref;          // meaningful in hi lanes: score = sum * c_code + off_col + reference
 
     // -- Value side. Raw sums to LDS; lane (tp, g) then owns tokens (2*tp, 2*tp+1) of channel block g:
@@ -420,8 +620,7 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
       const float s0 = lo_half(st.meta[2]), s1 = hi_half(st.meta[2]);
 #pragma unroll
       for (int hh = 0; hh < G; hh++) {
-        float off = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, off_col), hh));
-        off = live ? off : -INFINITY;          // a dead tile (past the end) contributes nothing
+        const float off = uniform_lane(off_col, hh);
         const float2_t sh = *reinterpret_cast<const float2_t*>(&L.s[hh][2 * tp]);
         const float2_t sl = *reinterpret_cast<const float2_t*>(&L.s[G + hh][2 * tp]);
         const float p0 = fast_exp2((sh[0] + sl[0]) * c_code + off);
@@ -458,22 +657,16 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
     }
     wave_lds_fence();   // the next tile's operand writes come after these reads
   };
+  auto process = [&](const Stage<KB, VB>& st) {
+    if constexpr (kSmall) process_small(st); else process_large(st);
+  };
 
-  if (p_end > p_begin) {
-    Stage<KB, VB> st[kDepth];
-    int it[kDepth];
-    // Past the end a wave re-reads the last tile (cache hit) and processes it as a dead tile: the load
-    // stream and the loop body stay uniform, which keeps the outstanding-load accounting exact.
-#pragma unroll
-    for (int s = 0; s < kDepth; s++) {
-      it[s] = grab();
-      st[s].load(up, it[s] < p_end ? it[s] : p_end - 1, lane);
-    }
+  if (has_packed) {
     while (it[0] < p_end) {      // a wave's items increase: it[0] is the oldest one in flight
 #pragma unroll
       for (int s = 0; s < kDepth; s++) {
         const int nxt = grab();
-        if (it[s] < p_end) process(st[s], true);   // past the end: skip the work, keep the load stream
+        if (it[s] < p_end) process(st[s]);   // past the end: skip the work, keep the load stream
         it[s] = nxt;
         st[s].load(up, nxt < p_end ? nxt : p_end - 1, lane);
       }
@@ -483,12 +676,29 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
   // ---- per-wave result: undo the field scaling, add hi and lo columns, add the zero-point term.
   // accZ: lanes with kq == 0 hold the zero-point sums of channel blocks 0..3, lanes with kq >= 1 the
   // sum of numerators (any register).
-  __syncthreads();   // every wave is done with its exchange area: the memory now holds the per-wave results
   float zsum[4];
+  float lsum;
+  if constexpr (kSmall) {
+    // running sums: the lanes of row 0 cover all tokens once (numerators), the lanes of row g hold the
+    // zero-point sums of channel block g; hi lanes take the whole term, lo lanes nothing
+    lsum = lwin;
 #pragma unroll
-  for (int g = 0; g < 4; g++) zsum[g] = __shfl(accZ[g], col);
-  float lsum = __shfl(accZ[0], 16 + col);
-  lsum += ror8(lsum);
+    for (int g = 0; g < 4; g++) zsum[g] = 0.0f;
+#pragma unroll
+    for (int hh = 0; hh < G; hh++) {
+      const float lr = row_sum(lacc[hh]), zr = row_sum(zacc[hh]);
+      const bool mine = col == hh;
+      const float lt = uniform_lane(lr, 0);   // cross-lane reads stay outside divergent code: the source lane must be active
+      lsum += mine ? lt : 0.0f;
+#pragma unroll
+      for (int g = 0; g < 4; g++) { const float t = uniform_lane(zr, 16 * g); zsum[g] = mine ? t : zsum[g]; }
+    }
+  } else {
+#pragma unroll
+    for (int g = 0; g < 4; g++) zsum[g] = __shfl(accZ[g], col);
+    lsum = __shfl(accZ[0], 16 + col);
+    lsum += ror8(lsum);
+  }
 #pragma unroll
   for (int m = 0; m < 8; m++) {
     const float sc = __builtin_ldexpf(1.0f, 24 - field_pos<VB>(m & 3));
@@ -505,14 +715,14 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
     }
   }
   if (col < G && kq == 0) { R.m[wave][col] = mref; R.l[wave][col] = lsum; }
-  __syncthreads();
 
-  for (int idx = tid; idx < G * kD; idx += kThreads) {
+  // combines the per-wave results of output idx = head * 128 + channel
+  auto combine = [&](int idx, float& M, float& Lsum, float& O) {
     const int hh = idx / kD, d = idx % kD;
-    float M = -INFINITY;
+    M = -INFINITY;
 #pragma unroll
     for (int w = 0; w < kWaves; w++) M = fmaxf(M, R.m[w][hh]);
-    float Lsum = 0.0f, O = 0.0f;
+    Lsum = 0.0f; O = 0.0f;
 #pragma unroll
     for (int w = 0; w < kWaves; w++) {
       const float mw = R.m[w][hh];
@@ -520,28 +730,58 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
       Lsum += R.l[w][hh] * f;
       O += R.o[w][hh][d] * f;
     }
-    if (a.n_splits == 1) {
-      a.out[((size_t)b * a.Hq + (size_t)jh * G + hh) * kD + d] = __builtin_bit_cast(uint16_t, (half_t)(O / Lsum));
+  };
+  uint16_t* outp = a.out + ((size_t)b * a.Hq + (size_t)jh * G) * kD;
+
+  if (a.n_splits == 1) {
+    if constexpr (G <= 2) {
+      // No barrier: a wave delivers its result and leaves; the last one to deliver combines them.
+      // (LDS serves a wave's operations in order, so its results are in place before its count.)
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+      int done = 0;
+      if (lane == 0) done = __hip_atomic_fetch_add(&s_done, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      done = __builtin_amdgcn_readfirstlane(done);
+      if (done != kWaves - 1) return;
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+#pragma unroll
+      for (int idx = lane; idx < G * kD; idx += kWave) {
+        float M, Lsum, O;
+        combine(idx, M, Lsum, O);
+        outp[idx] = __builtin_bit_cast(uint16_t, (half_t)(O / Lsum));
+      }
     } else {
-      // agent-scope stores: written through to the level all XCDs share (no cache-wide flush needed)
-      float* pp = a.part + (((size_t)u * a.n_splits + sp) * G + hh) * (kD + 2);
-      if (d == 0) { st_agent(pp, M); st_agent(pp + 1, Lsum); }
-      st_agent(pp + 2 + d, O);
+      __syncthreads();
+      for (int idx = tid; idx < G * kD; idx += kThreads) {
+        float M, Lsum, O;
+        combine(idx, M, Lsum, O);
+        outp[idx] = __builtin_bit_cast(uint16_t, (half_t)(O / Lsum));
+      }
     }
+    return;
   }
-  if (a.n_splits == 1) return;
+
+  __syncthreads();
+  for (int idx = tid; idx < G * kD; idx += kThreads) {
+    float M, Lsum, O;
+    combine(idx, M, Lsum, O);
+    // agent-scope stores: written through to the level all XCDs share (no cache-wide flush needed)
+    const int hh = idx / kD, d = idx % kD;
+    float* pp = a.part + (((size_t)u * a.n_splits + sp) * G + hh) * (kD + 2);
+    if (d == 0) { st_agent(pp, M); st_agent(pp + 1, Lsum); }
+    st_agent(pp + 2 + d, O);
+  }
 
   // ---- split merge: the last workgroup of the unit to arrive combines all partials
   // The partials were stored and are later loaded with agent scope, which the hardware keeps coherent
   // per access across the XCDs' L2s: waiting for the stores to complete is all the release needs.
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-  __syncthreads();
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's partial stores have completed ...
+  __syncthreads();                                     // ... and so have those of all waves, before the arrival is counted
   if (tid == 0) {
     const uint32_t prev = __hip_atomic_fetch_add(&a.counters[u], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    s_last = (prev == (uint32_t)a.n_splits - 1u);
+    s_done = (prev == (uint32_t)a.n_splits - 1u);   // reused as the "last workgroup" flag
   }
   __syncthreads();
-  if (!s_last) return;
+  if (!s_done) return;
   for (int idx = tid; idx < G * kD; idx += kThreads) {
     const int hh = idx / kD, d = idx % kD;
     const float* base = a.part + ((size_t)u * a.n_splits * G + hh) * (kD + 2);
