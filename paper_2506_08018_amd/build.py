@@ -13,7 +13,9 @@ COMMON = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall
 # per-source extra flags: the quantizer's arithmetic is specified operation by operation
 SOURCES = {
     "kvmix_quant.hip": ["-ffp-contract=off"],
-    "kvmix_attn.hip": [],
+    # tile claims are single-lane LDS atomics whose result is taken late; the wave-reduction rewrite of
+    # uniform atomics would put a wait right behind them
+    "kvmix_attn.hip": ["-mllvm", "-amdgpu-atomic-optimizer-strategy=None"],
     "kvmix_api.hip": [],
 }
 

@@ -57,6 +57,14 @@ __device__ __forceinline__ float row_sum(float v) {
   v += dpp_f<0x140>(v);   // row_mirror
   return v;
 }
+// maximum over the 16 lanes of each row; every lane of the row gets it
+__device__ __forceinline__ float row_max(float v) {
+  v = fmaxf(v, dpp_f<0xB1>(v));
+  v = fmaxf(v, dpp_f<0x4E>(v));
+  v = fmaxf(v, dpp_f<0x141>(v));
+  v = fmaxf(v, dpp_f<0x140>(v));
+  return v;
+}
 // sum over the 64 lanes of the wave as a wave-uniform value
 __device__ __forceinline__ float wave_sum(float v) {
   v = row_sum(v);
@@ -376,11 +384,15 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
     return fmaxf(mx, s[7]);
   };
 
-  auto grab = [&]() -> int {
-    int it = 0;
-    if (lane == 0) it = atomicAdd(&s_next, 1);
-    return __builtin_amdgcn_readfirstlane(it);
+  // claiming a tile: the counter update is issued early (lane 0) and its result taken after the tile in
+  // between has been worked on, so that the LDS round trip is not waited for
+  auto grab_issue = [&]() -> int {
+    int t = 0;
+    if (lane == 0) t = __hip_atomic_fetch_add(&s_next, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    return t;
   };
+  auto grab_take = [](int t) -> int { return __builtin_amdgcn_readfirstlane(t); };
+  auto grab = [&]() -> int { return grab_take(grab_issue()); };
 
   // ---- fp16 window tiles (few): taken round-robin by the waves before the packed stream.
   // A wave that started on packed tiles has no window tile; the nesting keeps its tile registers
@@ -665,8 +677,9 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
     while (it[0] < p_end) {      // a wave's items increase: it[0] is the oldest one in flight
 #pragma unroll
       for (int s = 0; s < kDepth; s++) {
-        const int nxt = grab();
+        const int ticket = grab_issue();
         if (it[s] < p_end) process(st[s]);   // past the end: skip the work, keep the load stream
+        const int nxt = grab_take(ticket);
         it[s] = nxt;
         st[s].load(up, nxt < p_end ? nxt : p_end - 1, lane);
       }
@@ -743,11 +756,26 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
       done = __builtin_amdgcn_readfirstlane(done);
       if (done != kWaves - 1) return;
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+      // lane w < kWaves holds wave w's reference and sum; the weights 2^(m_w - M) are computed once per head
+      // and handed out as scalars, then every lane adds up two channels over the waves
 #pragma unroll
-      for (int idx = lane; idx < G * kD; idx += kWave) {
-        float M, Lsum, O;
-        combine(idx, M, Lsum, O);
-        outp[idx] = __builtin_bit_cast(uint16_t, (half_t)(O / Lsum));
+      for (int hh = 0; hh < G; hh++) {
+        const bool has = lane < kWaves;
+        const float mw = has ? R.m[has ? lane : 0][hh] : -INFINITY;
+        const float lw = has ? R.l[has ? lane : 0][hh] : 0.0f;
+        const float M = uniform_lane(row_max(mw), 0);
+        const float fw = (mw == -INFINITY) ? 0.0f : fast_exp2(mw - M);
+        const float Lsum = uniform_lane(row_sum(lw * fw), 0);
+        float O0 = 0.0f, O1 = 0.0f;
+#pragma unroll
+        for (int w = 0; w < kWaves; w++) {
+          const float f = uniform_lane(fw, w);
+          O0 += R.o[w][hh][lane] * f;
+          O1 += R.o[w][hh][lane + kWave] * f;
+        }
+        const float inv = 1.0f / Lsum;
+        outp[hh * kD + lane] = __builtin_bit_cast(uint16_t, (half_t)(O0 * inv));
+        outp[hh * kD + lane + kWave] = __builtin_bit_cast(uint16_t, (half_t)(O1 * inv));
       }
     } else {
       __syncthreads();
