@@ -160,6 +160,17 @@ int kvmix_decode_attn(const kvmix_shape* shape, const kvmix_layer_cfg* cfg, cons
                       const kvmix_layer_cache* cache, float softmax_scale, uint16_t* out,
                       void* workspace, size_t workspace_bytes, int n_splits, void* stream);
 
+/* One decode step of a layer: kvmix_append followed by kvmix_decode_attn, same arguments and the same
+ * result. Unless the append makes the window overflow (then the two calls are made as they are), the
+ * append is done inside the attention launch: the workgroup that reads the window tile of the new slot
+ * takes the token from k_new / v_new and stores it into the window (Sec. 3.4 item 1 in spirit: no separate
+ * pass over the cache for the new token). Updates n_q, n_w, w0 in *cache (host). k_new, v_new must stay
+ * valid until the launch has run. */
+int kvmix_decode_step(const kvmix_shape* shape, const kvmix_layer_cfg* cfg,
+                      const uint16_t* k_new, const uint16_t* v_new, const uint16_t* q,
+                      kvmix_layer_cache* cache, float softmax_scale, uint16_t* out,
+                      void* workspace, size_t workspace_bytes, int n_splits, void* stream);
+
 /* Test helper: dequantize the n_q packed tokens back to fp32 (x = code*s_i + mn evaluated in
  * fp32), which = 0 for K, 1 for V; out is [units][n_q][128]. */
 int kvmix_dequant(const kvmix_shape* shape, const kvmix_layer_cfg* cfg,

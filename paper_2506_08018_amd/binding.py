@@ -56,6 +56,8 @@ def lib():
         L.kvmix_append.argtypes = [P, P, P, P, P, P]
         L.kvmix_decode_attn.restype = I
         L.kvmix_decode_attn.argtypes = [P, P, P, P, C.c_float, P, P, SZ, I, P]
+        L.kvmix_decode_step.restype = I
+        L.kvmix_decode_step.argtypes = [P, P, P, P, P, P, C.c_float, P, P, SZ, I, P]
         L.kvmix_dequant.restype = I
         L.kvmix_dequant.argtypes = [P, P, P, I, P, P]
         _lib = L
@@ -75,9 +77,12 @@ def _check(status, where):
         raise KVMixError(status, where)
 
 
-def _stream():
-    import torch
-    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+def _stream(stream=None):
+    """hipStream_t of torch's current stream, or of the given torch stream / raw handle."""
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream if isinstance(stream, int) else stream.cuda_stream)
 
 
 def cache_bytes(shape, cfg, T_cap, W_cap):
@@ -148,13 +153,24 @@ def append(shape, cfg, k_new, v_new, cache):
            "kvmix_append")
 
 
-def decode_attn(shape, cfg, q, cache, out, workspace=None, softmax_scale=0.0, n_splits=0):
-    """q, out: fp16 CUDA tensors [B][Hq][128], contiguous. workspace: uint8 CUDA tensor (zeroed once) or None."""
+def decode_attn(shape, cfg, q, cache, out, workspace=None, softmax_scale=0.0, n_splits=0, stream=None):
+    """q, out: fp16 CUDA tensors [B][Hq][128], contiguous. workspace: uint8 CUDA tensor (zeroed once) or None.
+    stream: torch stream or raw hipStream_t handle (default: torch's current stream)."""
     assert q.is_contiguous() and out.is_contiguous()
     wp, wn = (workspace.data_ptr(), workspace.numel() * workspace.element_size()) if workspace is not None else (None, 0)
     st = lib().kvmix_decode_attn(C.byref(shape), C.byref(cfg), q.data_ptr(), C.byref(cache.c), C.c_float(softmax_scale),
-                                 out.data_ptr(), wp, wn, n_splits, _stream())
+                                 out.data_ptr(), wp, wn, n_splits, _stream(stream))
     _check(st, "kvmix_decode_attn")
+    return out
+
+
+def decode_step(shape, cfg, k_new, v_new, q, cache, out, workspace=None, softmax_scale=0.0, n_splits=0, stream=None):
+    """append(k_new, v_new) followed by decode_attn(q), in one launch unless the window overflows."""
+    assert k_new.is_contiguous() and v_new.is_contiguous() and q.is_contiguous() and out.is_contiguous()
+    wp, wn = (workspace.data_ptr(), workspace.numel() * workspace.element_size()) if workspace is not None else (None, 0)
+    st = lib().kvmix_decode_step(C.byref(shape), C.byref(cfg), k_new.data_ptr(), v_new.data_ptr(), q.data_ptr(),
+                                 C.byref(cache.c), C.c_float(softmax_scale), out.data_ptr(), wp, wn, n_splits, _stream(stream))
+    _check(st, "kvmix_decode_step")
     return out
 
 

@@ -172,15 +172,22 @@ int kvmix_append(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const uint16
   return KVMIX_OK;
 }
 
-int kvmix_decode_attn(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const uint16_t* q, const kvmix_layer_cache* c,
-                      float softmax_scale, uint16_t* out, void* workspace, size_t workspace_bytes, int n_splits, void* stream) {
+}  // extern "C"
+
+namespace {
+
+// Validates and launches the attention kernel; with k_new / v_new the newest token of every unit is taken from
+// there (ring slot new_slot, not counted in n_w) and stored into the window by the kernel.
+int attention(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const uint16_t* q, const kvmix_layer_cache* c, int n_w,
+              const uint16_t* k_new, const uint16_t* v_new, int new_slot,
+              float softmax_scale, uint16_t* out, void* workspace, size_t workspace_bytes, int n_splits, void* stream) {
   int st = check_shape_cfg(sh, cfg);
   if (st) return st;
   if (!q || !out) return KVMIX_ERR_NULL;
   if (!aligned16(q) || !aligned16(out)) return KVMIX_ERR_ALIGN;
   st = check_cache(cfg, c, false);
   if (st) return st;
-  if (c->n_q + c->n_w < 1) return KVMIX_ERR_BAD_SHAPE;
+  if (c->n_q + n_w + (new_slot >= 0 ? 1 : 0) < 1 || n_w > c->W_cap) return KVMIX_ERR_BAD_SHAPE;
   const int units = sh->B * sh->Hkv, G = sh->Hq / sh->Hkv;
   const int n_items = c->W_cap / kTile + c->n_q / kTile;
   if (n_splits < 0 || n_splits > max_splits(sh)) return KVMIX_ERR_BAD_SHAPE;
@@ -204,13 +211,54 @@ int kvmix_decode_attn(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const u
   a.q = q; a.out = out;
   a.packed = c->packed;
   a.k_win = c->k_win; a.v_win = c->v_win;
-  a.tiles_cap = c->T_cap / kTile; a.W_cap = c->W_cap; a.n_tiles = c->n_q / kTile; a.n_w = c->n_w; a.w0 = c->w0;
+  a.k_new = k_new; a.v_new = v_new; a.k_win_w = c->k_win; a.v_win_w = c->v_win; a.new_slot = new_slot;
+  a.tiles_cap = c->T_cap / kTile; a.W_cap = c->W_cap; a.n_tiles = c->n_q / kTile; a.n_w = n_w; a.w0 = c->w0;
   a.Hq = sh->Hq; a.Hkv = sh->Hkv; a.n_splits = n_splits;
   const float scale = softmax_scale > 0.0f ? softmax_scale : 1.0f / std::sqrt((float)kD);
   a.scale_log2 = scale * 1.4426950408889634f;
   const int kb = cfg->k_bits == 16 ? 2 : cfg->k_bits, vb = cfg->v_bits == 16 ? 2 : cfg->v_bits;
   const hipError_t e = launch_decode_attn(a, kb, vb, G, units, (hipStream_t)stream);
   return e == hipSuccess ? KVMIX_OK : hip_fail(e);
+}
+
+}  // namespace
+
+extern "C" {
+
+int kvmix_decode_attn(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const uint16_t* q, const kvmix_layer_cache* c,
+                      float softmax_scale, uint16_t* out, void* workspace, size_t workspace_bytes, int n_splits, void* stream) {
+  const int st = check_shape_cfg(sh, cfg);   // before the cache struct is looked at
+  if (st) return st;
+  if (!q || !out) return KVMIX_ERR_NULL;
+  if (!aligned16(q) || !aligned16(out)) return KVMIX_ERR_ALIGN;
+  if (!c) return KVMIX_ERR_NULL;
+  return attention(sh, cfg, q, c, c->n_w, nullptr, nullptr, -1, softmax_scale, out, workspace, workspace_bytes, n_splits, stream);
+}
+
+int kvmix_decode_step(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const uint16_t* k_new, const uint16_t* v_new,
+                      const uint16_t* q, kvmix_layer_cache* c, float softmax_scale, uint16_t* out,
+                      void* workspace, size_t workspace_bytes, int n_splits, void* stream) {
+  int st = check_shape_cfg(sh, cfg);
+  if (st) return st;
+  if (!k_new || !v_new || !c) return KVMIX_ERR_NULL;
+  const bool flush = cfg->k_bits != 16 && c->n_w + 1 == cfg->window + kTile;
+  if (flush) {
+    // the 32 oldest window tokens move to the packed part before the attention reads them: two kernels, then attention
+    st = kvmix_append(sh, cfg, k_new, v_new, c, stream);
+    if (st) return st;
+    return attention(sh, cfg, q, c, c->n_w, nullptr, nullptr, -1, softmax_scale, out, workspace, workspace_bytes, n_splits, stream);
+  }
+  st = check_cache(cfg, c, cfg->k_bits != 16);
+  if (st) return st;
+  if (c->n_w >= c->W_cap) return KVMIX_ERR_BAD_SHAPE;
+  if (cfg->k_bits != 16 && c->W_cap < cfg->window + kTile) return KVMIX_ERR_BAD_SHAPE;
+  if (!aligned16(k_new) || !aligned16(v_new)) return KVMIX_ERR_ALIGN;
+  const int slot = (c->w0 + c->n_w) % c->W_cap;
+  // the kernel's window count excludes the new token: it is added as a term of its own (and stored)
+  st = attention(sh, cfg, q, c, c->n_w, k_new, v_new, slot, softmax_scale, out, workspace, workspace_bytes, n_splits, stream);
+  if (st) return st;
+  c->n_w += 1;
+  return KVMIX_OK;
 }
 
 int kvmix_dequant(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const kvmix_layer_cache* c, int which, float* out, void* stream) {

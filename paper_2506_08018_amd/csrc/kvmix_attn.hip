@@ -204,15 +204,19 @@ __device__ __forceinline__ void st_agent(float* p, float v) { __hip_atomic_store
 __device__ __forceinline__ float ld_agent(const float* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 
 // fp32 pair -> packed fp16 pairs (hi, lo) with hi + lo == x to ~22 bits
+// The hi parts come from the truncating packed conversion, an intrinsic of its own: written as a plain
+// cast, the multiply that produced x may get fused into one of the two uses of the hi part only, and the
+// stored hi part and the one the lo part refers to then differ by a double rounding.
 __device__ __forceinline__ void split_pair(float x0, float x1, uint32_t& hi, uint32_t& lo) {
-  const half_t h0 = (half_t)x0, h1 = (half_t)x1;
-  const half_t l0 = (half_t)(x0 - (float)h0), l1 = (half_t)(x1 - (float)h1);
-  const half2_t hv = {h0, h1}, lv = {l0, l1};
+  const half2_t hv = __builtin_bit_cast(half2_t, __builtin_amdgcn_cvt_pkrtz(x0, x1));
+  const half_t l0 = (half_t)(x0 - (float)hv[0]), l1 = (half_t)(x1 - (float)hv[1]);
+  const half2_t lv = {l0, l1};
   hi = __builtin_bit_cast(uint32_t, hv);
   lo = __builtin_bit_cast(uint32_t, lv);
 }
 __device__ __forceinline__ half_t split_part(float x, bool lo_part) {
-  const half_t hi = (half_t)x;
+  const half2_t hv = __builtin_bit_cast(half2_t, __builtin_amdgcn_cvt_pkrtz(x, 0.0f));
+  const half_t hi = hv[0];
   const half_t lo = (half_t)(x - (float)hi);
   return lo_part ? lo : hi;
 }
@@ -284,6 +288,13 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
 #pragma unroll
     for (int hh = 0; hh < G; hh++) qraw[hh] = reinterpret_cast<const uint32_t*>(qbase + (size_t)hh * kD)[lane];
   }
+
+  // Fused append: the newest token of the unit is not in the window arrays yet (the kernel's n_w does not
+  // count it; its ring slot is masked like any slot past the end). One wave of the unit's first split adds
+  // its term to the running softmax by hand and stores it into the window for the steps to come.
+  const bool extra = a.new_slot >= 0 && sp == 0 && wave == kWaves - 1;   // wave-uniform
+  uint32_t knew_pair = 0;     // Key channels 2*lane, 2*lane+1 (requested now, the Value row when it is needed)
+  if (extra) knew_pair = reinterpret_cast<const uint32_t*>(a.k_new + (size_t)u * kD)[lane];
 
   constexpr uint32_t kRecBytes = (uint32_t)(record_words(KB, VB) * 4);
   const rsrc_t up = make_rsrc(reinterpret_cast<const char*>(a.packed) + (size_t)u * a.tiles_cap * kRecBytes, (uint32_t)a.tiles_cap * kRecBytes);
@@ -464,6 +475,57 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
     }
   }
   const float inv_c_code = 1.0f / c_code;
+
+  // ---- the token that is being appended (see above): score by packed dot products and a wave sum, then its
+  // term of the running softmax in the accumulators' units (code domain: 2^(field position - 24))
+  if (extra) {
+    u32x2_t vnew[8];               // Value channels 16*m + 4*kq .. +3
+#pragma unroll
+    for (int m = 0; m < 8; m++) vnew[m] = *reinterpret_cast<const u32x2_t*>(a.v_new + (size_t)u * kD + 16 * m + 4 * kq);
+    float s_lane = -INFINITY;      // the score of the lane's head, log2 domain
+#pragma unroll
+    for (int hh = 0; hh < G; hh++) {
+      const float sc = wave_sum(__builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, qraw[hh]), __builtin_bit_cast(half2_t, knew_pair), 0.0f, false)) * c_plain;
+      s_lane = (h == hh) ? sc : s_lane;
+      if constexpr (kSmall) {
+        if (sc > mref_u[hh]) {        // wave-uniform
+          const float mnew = sc + kRefMargin;
+          const float f = fast_exp2(mref_u[hh] - mnew);
+          mref_u[hh] = mnew;
+          lacc[hh] *= f; zacc[hh] *= f;
+          if (h == hh) {
+            mref = mnew;
+            lwin *= f;
+#pragma unroll
+            for (int m = 0; m < 8; m++) acc[m] *= f;
+          }
+        }
+      }
+    }
+    if constexpr (!kSmall) raise_reference(s_lane);
+    const float pn = (col_valid && !lo_part) ? fast_exp2(s_lane - mref) : 0.0f;
+    if constexpr (kSmall) lwin += pn;                    // every lane of a hi column carries the column's sum
+    else accZ[0] += (kq == 1) ? pn : 0.0f;               // where the sum of numerators is read from at the end
+#pragma unroll
+    for (int m = 0; m < 8; m++) {
+      const float unit = __builtin_ldexpf(1.0f, field_pos<VB>(m & 3) - 24);
+#pragma unroll
+      for (int r = 0; r < 4; r++) {
+        const uint32_t w = vnew[m][r >> 1];
+        float v = (r & 1) ? hi_half(w) : lo_half(w);
+        if constexpr (VB == 3) {   // the final 7/3 step factor of channels 10 / 21 applies to codes only
+          const int dd = 16 * (m & 1) + 4 * kq + r;
+          if (dd == 10 || dd == 21) v *= (3.0f / 7.0f);
+        }
+        acc[m][r] += pn * v * unit;
+      }
+    }
+    // the append itself
+    for (int d = lane; d < kD; d += kWave) {
+      a.k_win_w[((size_t)u * a.W_cap + a.new_slot) * kD + d] = a.k_new[(size_t)u * kD + d];
+      a.v_win_w[((size_t)u * kD + d) * a.W_cap + a.new_slot] = a.v_new[(size_t)u * kD + d];
+    }
+  }
 
   auto process_small = [&](const Stage<KB, VB>& st) {
     // -- Key side. Lane owns channels 2*lane, 2*lane+1: scale-folded query to LDS, zero-point term by dot product

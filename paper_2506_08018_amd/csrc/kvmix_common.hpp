@@ -84,6 +84,11 @@ struct AttnArgs {
   const uint16_t* q; uint16_t* out;
   const uint32_t* packed;
   const uint16_t* k_win; const uint16_t* v_win;
+  // fused append: the newest token of every unit ([units][128] each) is not in the window arrays yet and
+  // not counted in n_w; one wave per unit adds its term and stores it into ring slot new_slot
+  const uint16_t* k_new; const uint16_t* v_new;
+  uint16_t* k_win_w; uint16_t* v_win_w;
+  int new_slot;           // -1: nothing to append
   float* part;            // split partials: [units][n_splits][G][kD + 2]
   uint32_t* counters;     // [units] arrival counters (zero before and after every call)
   int tiles_cap, W_cap, n_tiles, n_w, w0;

@@ -126,6 +126,39 @@ def test_append_and_flush_match_oracle(kb, vb, G):
     assert np.array_equal(bits_of(gc.v_win, np.uint16).reshape(rc.v_win.shape), rc.v_win)
 
 
+@pytest.mark.parametrize("kb,vb,G,n_splits", [(2, 2, 1, 0), (2, 3, 2, 3), (3, 4, 4, 1), (4, 2, 8, 2), (16, 16, 2, 0)])
+def test_decode_step_equals_append_then_attention(kb, vb, G, n_splits):
+    """The fused step (append inside the attention launch, two launches + attention when the window overflows)
+    against the oracle's append followed by its attention, at every step across two flushes; the window
+    arrays and the tile records end up identical too."""
+    import torch
+    import paper_2506_08018_amd as kv
+    print(f"case decode_step kb={kb} vb={vb} G={G} splits={n_splits}", flush=True)
+    B, Hkv, W, T0, steps = 2, 2, 32, 96 + 7, 70
+    q, k, v = synth.gen_layer_numpy(810 + G, 0, B, Hkv * G, Hkv, T0 + steps)
+    W_cap = 64 if kb != 16 else 192
+    _, _, _, rc, gc, shape, cfg = make_pair(B, Hkv * G, Hkv, T0, W, kb, vb, T_cap=256, W_cap=W_cap, q_k_v=(q, k[:, :, :T0], v[:, :, :T0]))
+    kt, vt = torch.from_numpy(k).cuda(), torch.from_numpy(v).cuda()
+    ws = torch.zeros(kv.workspace_bytes(shape, 512), dtype=torch.uint8, device="cuda")
+    rng = np.random.default_rng(5)
+    for s in range(steps):
+        qs = (q.astype(np.float32) * rng.uniform(0.5, 1.5)).astype(np.float16)      # a fresh query every step
+        qt = torch.from_numpy(qs).cuda()
+        out = torch.zeros_like(qt)
+        assert rc.append(u16(k[:, :, T0 + s]), u16(v[:, :, T0 + s])) == 0
+        st, want = rc.decode_attn(u16(qs))
+        assert st == 0
+        kv.decode_step(shape, cfg, kt[:, :, T0 + s].contiguous(), vt[:, :, T0 + s].contiguous(), qt, gc, out, ws, n_splits=n_splits)
+        torch.cuda.synchronize()
+        assert (gc.n_q, gc.n_w, gc.w0) == (rc.n_q, rc.n_w, rc.w0)
+        assert_attn_close(t16(out), want, f"decode_step {s} (n_q {gc.n_q}, n_w {gc.n_w})", tight=True)
+    assert not ws[: 4 * shape.units].any()
+    if kb != 16:
+        assert_cache_equal(rc, gc)
+    assert np.array_equal(bits_of(gc.k_win, np.uint16).reshape(rc.k_win.shape), rc.k_win)
+    assert np.array_equal(bits_of(gc.v_win, np.uint16).reshape(rc.v_win.shape), rc.v_win)
+
+
 @pytest.mark.parametrize("kb,vb,G", [(2, 2, 1), (3, 4, 4), (4, 2, 8)])
 def test_many_tiles_per_wave(kb, vb, G):
     """Long context in few workgroups: every wave runs many iterations of its prefetch loop."""
