@@ -57,8 +57,7 @@
  *   Unused bits are zero.
  *
  * Recent window (fp16, ring buffer of W_cap slots, W_cap % 32 == 0, W_cap >= window + 32)
- *   k_win : [units][W_cap][128]   (channel contiguous)
- *   v_win : [units][128][W_cap]   (slot contiguous: the Value window is stored transposed)
+ *   k_win, v_win : [units][W_cap][128]   (channel contiguous: appending a token writes one full row of each)
  *   The n_w valid tokens sit in slots (w0 + r) % W_cap, r = 0..n_w-1, oldest first;
  *   w0 % 32 == 0. Both windows must hold finite values in every slot (zero-fill at allocation).
  */

@@ -314,15 +314,15 @@ int kvmix_ref_append(const ref_shape* sh, const ref_layer_cfg* cfg, const uint16
   for (int u = 0; u < units; u++)
     for (int d = 0; d < D_HEAD; d++) {
       c->k_win[((size_t)u * W + slot) * D_HEAD + d] = k_new[(size_t)u * D_HEAD + d];
-      c->v_win[((size_t)u * D_HEAD + d) * W + slot] = v_new[(size_t)u * D_HEAD + d];
+      c->v_win[((size_t)u * W + slot) * D_HEAD + d] = v_new[(size_t)u * D_HEAD + d];
     }
   c->n_w += 1;
   if (cfg->k_bits != 16 && c->n_w == cfg->window + TILE_TOKENS) {
     if (c->n_q + TILE_TOKENS > c->T_cap) return REF_ERR_BAD_SHAPE;
     /* the oldest 32 tokens are slots w0 .. w0+31 (w0 and W_cap are multiples of 32) */
-    st = quantize_pack_strided(sh, cfg, c->k_win + (size_t)c->w0 * D_HEAD, c->v_win + c->w0,
+    st = quantize_pack_strided(sh, cfg, c->k_win + (size_t)c->w0 * D_HEAD, c->v_win + (size_t)c->w0 * D_HEAD,
                                D_HEAD, 1, (int64_t)sh->Hkv * W * D_HEAD, (int64_t)W * D_HEAD,
-                               1, W, (int64_t)sh->Hkv * D_HEAD * W, (int64_t)D_HEAD * W,
+                               D_HEAD, 1, (int64_t)sh->Hkv * W * D_HEAD, (int64_t)W * D_HEAD,
                                TILE_TOKENS, c->n_q, c);
     if (st) return st;
     c->n_q += TILE_TOKENS;
@@ -381,7 +381,7 @@ int kvmix_ref_decode_attn(const ref_shape* sh, const ref_layer_cfg* cfg, const u
       int slot = (c->w0 + r) % W;
       for (int d = 0; d < D_HEAD; d++) {
         Kt[(size_t)(c->n_q + r) * D_HEAD + d] = kvmix_ref_h2d(c->k_win[((size_t)u * W + slot) * D_HEAD + d]);
-        Vt[(size_t)(c->n_q + r) * D_HEAD + d] = kvmix_ref_h2d(c->v_win[((size_t)u * D_HEAD + d) * W + slot]);
+        Vt[(size_t)(c->n_q + r) * D_HEAD + d] = kvmix_ref_h2d(c->v_win[((size_t)u * W + slot) * D_HEAD + d]);
       }
     }
     for (int hg = 0; hg < G; hg++) {

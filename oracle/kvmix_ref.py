@@ -149,7 +149,7 @@ class RefCache:
         self.kb, self.vb = kb, vb
         self.packed = np.zeros((self.units, tiles, record_words(kb, vb)), np.uint32)
         self.k_win = np.zeros((self.units, W_cap, 128), np.uint16)
-        self.v_win = np.zeros((self.units, 128, W_cap), np.uint16)
+        self.v_win = np.zeros((self.units, W_cap, 128), np.uint16)
         self.c = _Cache(_ptr(self.packed).value, _ptr(self.k_win).value, _ptr(self.v_win).value, T_cap, W_cap, 0, 0, 0)
 
     def fields(self):
@@ -189,7 +189,7 @@ class RefCache:
         v = np.asarray(v, dtype=np.uint16).reshape(self.units, n, 128)
         assert n <= self.c.W_cap
         self.k_win[:, :n, :] = k
-        self.v_win[:, :, :n] = v.transpose(0, 2, 1)
+        self.v_win[:, :n, :] = v
         self.c.n_w = n
         self.c.w0 = 0
 

@@ -126,9 +126,9 @@ class LayerCache:
         n = k.shape[2]
         assert n <= W
         kw = self.k_win.view(torch.float16).view(units, W, 128)
-        vw = self.v_win.view(torch.float16).view(units, 128, W)
+        vw = self.v_win.view(torch.float16).view(units, W, 128)
         kw[:, :n, :] = k.reshape(units, n, 128)
-        vw[:, :, :n] = v.reshape(units, n, 128).transpose(1, 2)
+        vw[:, :n, :] = v.reshape(units, n, 128)
         self.c.n_w = n
         self.c.w0 = 0
 

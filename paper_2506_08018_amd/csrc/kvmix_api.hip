@@ -127,11 +127,11 @@ int kvmix_quantize_pack(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const
   QuantArgs a{};
   a.k = k_fp16; a.v = v_fp16;
   a.k_tok = token_stride; a.k_unit_b = batch_stride; a.k_unit_h = head_stride;
-  a.v_tok = token_stride; a.v_chan = 1; a.v_unit_b = batch_stride; a.v_unit_h = head_stride;
+  a.v_tok = token_stride; a.v_unit_b = batch_stride; a.v_unit_h = head_stride;
   fill_quant_dst(a, c);
   a.tile0 = t0 / kTile;
   a.Hkv = sh->Hkv;
-  const hipError_t e = launch_quantize_pack(a, cfg->k_bits, cfg->v_bits, false, n_tokens / kTile, sh->B * sh->Hkv, (hipStream_t)stream);
+  const hipError_t e = launch_quantize_pack(a, cfg->k_bits, cfg->v_bits, n_tokens / kTile, sh->B * sh->Hkv, (hipStream_t)stream);
   return e == hipSuccess ? KVMIX_OK : hip_fail(e);
 }
 
@@ -157,13 +157,13 @@ int kvmix_append(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const uint16
     // the oldest 32 tokens are ring slots w0 .. w0+31; same quantizer, destination tile n_q/32
     QuantArgs a{};
     a.k = c->k_win + (size_t)c->w0 * kD;
-    a.v = c->v_win + c->w0;
+    a.v = c->v_win + (size_t)c->w0 * kD;
     a.k_tok = kD; a.k_unit_b = (int64_t)sh->Hkv * W * kD; a.k_unit_h = (int64_t)W * kD;
-    a.v_tok = 1; a.v_chan = W; a.v_unit_b = (int64_t)sh->Hkv * kD * W; a.v_unit_h = (int64_t)kD * W;
+    a.v_tok = kD; a.v_unit_b = (int64_t)sh->Hkv * W * kD; a.v_unit_h = (int64_t)W * kD;
     fill_quant_dst(a, c);
     a.tile0 = c->n_q / kTile;
     a.Hkv = sh->Hkv;
-    e = launch_quantize_pack(a, cfg->k_bits, cfg->v_bits, true, 1, units, (hipStream_t)stream);
+    e = launch_quantize_pack(a, cfg->k_bits, cfg->v_bits, 1, units, (hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(e);
     c->n_q += kTile;
     c->n_w -= kTile;

@@ -246,7 +246,11 @@ template <int KB, int VB, int G>
 __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnArgs a) {
   constexpr int kWaves = waves_for(G);
   constexpr int kThreads = kWaves * kWave;
-  __shared__ WaveLds<G> s_wave[kWaves];
+  // per wave: the exchange area of the packed tiles; before that, the staging area in which a window tile's
+  // Value rows (token-major in memory) are turned into matrix-core operands (8 consecutive tokens per lane)
+  constexpr int kTPitch = kD + 8;   // fp16 elements per staged row (272 B: 16-byte aligned rows)
+  union WaveArea { WaveLds<G> x; uint16_t t[kTile][kTPitch]; };
+  __shared__ WaveArea s_wave[kWaves];
   __shared__ MergeLds<G> R;
   __shared__ int s_next;   // next unclaimed packed tile of this workgroup
   __shared__ int s_done;   // waves that have delivered their result
@@ -258,7 +262,8 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
   const bool col_valid = h < G;
   const int sp = blockIdx.x, u = blockIdx.y;
   const int b = u / a.Hkv, jh = u % a.Hkv;
-  WaveLds<G>& L = s_wave[wave];
+  WaveLds<G>& L = s_wave[wave].x;
+  uint16_t (&T)[kTile][kTPitch] = s_wave[wave].t;
   const int row = col_valid ? (lo_part ? G + h : h) : WaveLds<G>::kRows;   // operand row of this lane's column
 
   // work items of this split: window tiles first, then packed tiles
@@ -314,13 +319,14 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
     }
   }
 
-  // window tile wi of the ring: registers of the two MFMA A operands (Keys: rows = tokens, Values: rows = channels)
-  struct WinTile { half8_t Ak[2][4], Av[8]; };
+  // window tile wi of the ring: the Key rows as MFMA A operands (rows = tokens), the Value rows as loaded:
+  // 16-byte piece lane + 64*j of the tile's 8 KiB, i.e. token 4*j + kq, channels 8*col .. 8*col+7
+  struct WinTile { half8_t Ak[2][4]; u32x4_t Vr[8]; };
   auto win_first = [&](int wi) { return (wi * kTile - a.w0 + a.W_cap) % a.W_cap; };   // ring rank of the tile's first slot
   auto win_load = [&](int wi, WinTile& w) {
     const int slot0 = wi * kTile;
     const uint16_t* kw = a.k_win + ((size_t)u * a.W_cap + slot0) * kD;
-    const uint16_t* vw = a.v_win + (size_t)u * kD * a.W_cap + slot0 + 8 * kq;
+    const uint16_t* vw = a.v_win + ((size_t)u * a.W_cap + slot0) * kD;
 #pragma unroll
     for (int m = 0; m < 2; m++) {
       const int tau = 8 * (col >> 2) + 4 * m + (col & 3);   // row `col` of M-tile m
@@ -328,13 +334,7 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
       for (int ks = 0; ks < 4; ks++) w.Ak[m][ks] = *reinterpret_cast<const half8_t*>(kw + (size_t)tau * kD + 32 * ks + 8 * kq);
     }
 #pragma unroll
-    for (int m = 0; m < 4; m++) w.Av[m] = *reinterpret_cast<const half8_t*>(vw + (size_t)(16 * m + col) * a.W_cap);
-  };
-  // second half of the Value rows: requested once the Key rows have been consumed (fewer registers in flight)
-  auto win_load_rest = [&](int wi, WinTile& w) {
-    const uint16_t* vw = a.v_win + (size_t)u * kD * a.W_cap + wi * kTile + 8 * kq;
-#pragma unroll
-    for (int m = 4; m < 8; m++) w.Av[m] = *reinterpret_cast<const half8_t*>(vw + (size_t)(16 * m + col) * a.W_cap);
+    for (int j = 0; j < 8; j++) w.Vr[j] = *reinterpret_cast<const u32x4_t*>(vw + (size_t)(4 * j + kq) * kD + 8 * col);
   };
   WinTile wt;
   int wi = win_begin + wave;
@@ -343,11 +343,6 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
   if (wi < win_end) win_load(wi, wt);
 
   if (tid == 0) { s_next = p_begin + kDepth * n_early; s_done = 0; }
-  // zero the wave's exchange area: rows of unused columns stay zero for the whole kernel
-  {
-    u32x4_t* z = reinterpret_cast<u32x4_t*>(&L);
-    for (int i = lane; i < (int)(sizeof(WaveLds<G>) / 16); i += kWave) z[i] = u32x4_t{0, 0, 0, 0};
-  }
   __syncthreads();   // the only workgroup barrier before the results are merged: the counters are set
 
   float qc[G][2];     // q prescaled by 2^-field_pos of the lane's channel block
@@ -412,13 +407,14 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
   while (wi < win_end) {
     const int first = win_first(wi);
     const half8_t (&Ak)[2][4] = wt.Ak;
-    const half8_t (&Av)[8] = wt.Av;
     float4_t S[2] = {float4_t{0, 0, 0, 0}, float4_t{0, 0, 0, 0}};
 #pragma unroll
     for (int m = 0; m < 2; m++)
 #pragma unroll
       for (int ks = 0; ks < 4; ks++) S[m] = mfma16(Ak[m][ks], qB[ks], S[m]);
-    win_load_rest(wi, wt);
+    // Value rows into the staging area as loaded (their registers are free again before the softmax)
+#pragma unroll
+    for (int j = 0; j < 8; j++) *reinterpret_cast<u32x4_t*>(&T[4 * j + kq][8 * col]) = wt.Vr[j];
     float x[8], p[8];
 #pragma unroll
     for (int m = 0; m < 2; m++)
@@ -433,9 +429,14 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
 #pragma unroll
     for (int e = 0; e < 8; e++) PB[e] = split_part(col_valid ? p[e] : 0.0f, lo_part);
     accZ = mfma16(col >= 4 ? ones8 : zero8, PB, accZ);   // rows 4..15 accumulate the sum of numerators
+    // Value rows back from the staging area, channel by channel
+    wave_lds_fence();
 #pragma unroll
     for (int m = 0; m < 8; m++) {
-      float4_t t = mfma16(Av[m], PB, float4_t{0, 0, 0, 0});
+      half8_t Avm;
+#pragma unroll
+      for (int e = 0; e < 8; e++) Avm[e] = __builtin_bit_cast(half_t, T[8 * kq + e][16 * m + col]);
+      float4_t t = mfma16(Avm, PB, float4_t{0, 0, 0, 0});
       if constexpr (VB == 3) {   // the final 7/3 step factor of channels 10 / 21 applies to codes only
 #pragma unroll
         for (int r = 0; r < 4; r++) {
@@ -445,6 +446,7 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
       }
       acc[m] += t * __builtin_ldexpf(1.0f, field_pos<VB>(m & 3) - 24);
     }
+    wave_lds_fence();   // the staging area is free again
     wi += kWaves;
     while (wi < win_end && win_first(wi) >= a.n_w) wi += kWaves;
     if (wi < win_end) win_load(wi, wt);
@@ -457,6 +459,14 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
     }
   }
   }
+
+  // zero the wave's exchange area (it shared its memory with the staging area): the rows of unused
+  // operand columns stay zero from here on
+  {
+    u32x4_t* z = reinterpret_cast<u32x4_t*>(&L);
+    for (int i = lane; i < (int)(sizeof(WaveLds<G>) / 16); i += kWave) z[i] = u32x4_t{0, 0, 0, 0};
+  }
+  wave_lds_fence();
 
   // ---- small query groups (G <= 2): the matrix core's columns are nearly empty, so the per-tile extras
   // (Key zero-point term, Value zero-point term, sum of numerators) are cheaper on the vector unit:
@@ -523,7 +533,7 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
     // the append itself
     for (int d = lane; d < kD; d += kWave) {
       a.k_win_w[((size_t)u * a.W_cap + a.new_slot) * kD + d] = a.k_new[(size_t)u * kD + d];
-      a.v_win_w[((size_t)u * kD + d) * a.W_cap + a.new_slot] = a.v_new[(size_t)u * kD + d];
+      a.v_win_w[((size_t)u * a.W_cap + a.new_slot) * kD + d] = a.v_new[(size_t)u * kD + d];
     }
   }
 

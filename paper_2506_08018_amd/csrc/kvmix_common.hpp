@@ -62,7 +62,7 @@ __host__ __device__ inline void value_td(int l, int j, int hh, int slot, int& ta
 struct QuantArgs {
   const uint16_t* k; const uint16_t* v;
   int64_t k_tok, k_unit_b, k_unit_h;            // Key input: channel stride 1
-  int64_t v_tok, v_chan, v_unit_b, v_unit_h;    // Value input: channel stride 1 or token stride 1
+  int64_t v_tok, v_unit_b, v_unit_h;            // Value input: channel stride 1
   uint32_t* packed;
   int tiles_cap;   // tiles per unit in the packed cache
   int tile0;       // first destination tile
@@ -96,7 +96,7 @@ struct AttnArgs {
   float scale_log2;       // softmax_scale * log2(e)
 };
 
-hipError_t launch_quantize_pack(const QuantArgs& a, int k_bits, int v_bits, bool v_token_contig,
+hipError_t launch_quantize_pack(const QuantArgs& a, int k_bits, int v_bits,
                                 int n_tiles, int units, hipStream_t s);
 hipError_t launch_dequant(const DequantArgs& a, int units, hipStream_t s);
 hipError_t launch_append(const AppendArgs& a, hipStream_t s);

@@ -105,7 +105,7 @@ __device__ __forceinline__ void pack_tile(const uint8_t* cs /*[32][128]*/, uint3
 // One workgroup (256 threads) quantizes and packs the Key tile and the Value tile of one
 // (unit, 32-token tile): waves 0-1 own the 128 Key groups (one channel each), waves 2-3 the
 // 128 Value groups (one (token, 32-channel block) each).
-template <int KB, int VB, bool V_TOKEN_CONTIG>
+template <int KB, int VB>
 __global__ __launch_bounds__(256) void quantize_pack_kernel(QuantArgs a) {
   __shared__ __attribute__((aligned(16))) uint16_t xs[2][kTile * kRow];
   __shared__ __attribute__((aligned(16))) uint8_t cs[2][kTile * kD];
@@ -121,17 +121,8 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(QuantArgs a) {
     const int tau = (tid >> 4) + 16 * p, dc = (tid & 15) * 8;
     const u32x4_t kv = *reinterpret_cast<const u32x4_t*>(kin + (int64_t)tau * a.k_tok + dc);
     *reinterpret_cast<u32x4_t*>(&xs[0][tau * kRow + dc]) = kv;
-    if (!V_TOKEN_CONTIG) {
-      const u32x4_t vv = *reinterpret_cast<const u32x4_t*>(vin + (int64_t)tau * a.v_tok + dc);
-      *reinterpret_cast<u32x4_t*>(&xs[1][tau * kRow + dc]) = vv;
-    } else {
-      // Value source stored [channel][token]: 8 consecutive tokens of one channel per load
-      const int d = (tid >> 2) + 64 * p, tc = (tid & 3) * 8;
-      const u32x4_t vv = *reinterpret_cast<const u32x4_t*>(vin + (int64_t)d * a.v_chan + tc);
-      const uint16_t* e = reinterpret_cast<const uint16_t*>(&vv);
-#pragma unroll
-      for (int t = 0; t < 8; t++) xs[1][(tc + t) * kRow + d] = e[t];
-    }
+    const u32x4_t vv = *reinterpret_cast<const u32x4_t*>(vin + (int64_t)tau * a.v_tok + dc);
+    *reinterpret_cast<u32x4_t*>(&xs[1][tau * kRow + dc]) = vv;
   }
   __syncthreads();
 
@@ -203,36 +194,35 @@ __global__ __launch_bounds__(256) void dequant_kernel(DequantArgs a) {
   }
 }
 
-// New token of every unit into ring slot `slot` of the fp16 window (Value window transposed).
+// New token of every unit into ring slot `slot` of the two fp16 windows.
 __global__ __launch_bounds__(128) void append_kernel(AppendArgs a) {
   const int u = blockIdx.x, d = threadIdx.x;
   a.k_win[((size_t)u * a.W_cap + a.slot) * kD + d] = a.k_new[(size_t)u * kD + d];
-  a.v_win[((size_t)u * kD + d) * a.W_cap + a.slot] = a.v_new[(size_t)u * kD + d];
+  a.v_win[((size_t)u * a.W_cap + a.slot) * kD + d] = a.v_new[(size_t)u * kD + d];
 }
 
 template <int KB, int VB>
-hipError_t launch_qp(const QuantArgs& a, bool v_token_contig, dim3 grid, hipStream_t s) {
-  if (v_token_contig) quantize_pack_kernel<KB, VB, true><<<grid, 256, 0, s>>>(a);
-  else quantize_pack_kernel<KB, VB, false><<<grid, 256, 0, s>>>(a);
+hipError_t launch_qp(const QuantArgs& a, dim3 grid, hipStream_t s) {
+  quantize_pack_kernel<KB, VB><<<grid, 256, 0, s>>>(a);
   return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_quantize_pack(const QuantArgs& a, int k_bits, int v_bits, bool v_token_contig,
+hipError_t launch_quantize_pack(const QuantArgs& a, int k_bits, int v_bits,
                                 int n_tiles, int units, hipStream_t s) {
   if (n_tiles == 0 || units == 0) return hipSuccess;
   const dim3 grid(n_tiles, units);
   switch (k_bits * 10 + v_bits) {
-    case 22: return launch_qp<2, 2>(a, v_token_contig, grid, s);
-    case 23: return launch_qp<2, 3>(a, v_token_contig, grid, s);
-    case 24: return launch_qp<2, 4>(a, v_token_contig, grid, s);
-    case 32: return launch_qp<3, 2>(a, v_token_contig, grid, s);
-    case 33: return launch_qp<3, 3>(a, v_token_contig, grid, s);
-    case 34: return launch_qp<3, 4>(a, v_token_contig, grid, s);
-    case 42: return launch_qp<4, 2>(a, v_token_contig, grid, s);
-    case 43: return launch_qp<4, 3>(a, v_token_contig, grid, s);
-    case 44: return launch_qp<4, 4>(a, v_token_contig, grid, s);
+    case 22: return launch_qp<2, 2>(a, grid, s);
+    case 23: return launch_qp<2, 3>(a, grid, s);
+    case 24: return launch_qp<2, 4>(a, grid, s);
+    case 32: return launch_qp<3, 2>(a, grid, s);
+    case 33: return launch_qp<3, 3>(a, grid, s);
+    case 34: return launch_qp<3, 4>(a, grid, s);
+    case 42: return launch_qp<4, 2>(a, grid, s);
+    case 43: return launch_qp<4, 3>(a, grid, s);
+    case 44: return launch_qp<4, 4>(a, grid, s);
   }
   return hipErrorInvalidValue;
 }
