@@ -412,9 +412,10 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
     for (int m = 0; m < 2; m++)
 #pragma unroll
       for (int ks = 0; ks < 4; ks++) S[m] = mfma16(Ak[m][ks], qB[ks], S[m]);
-    // Value rows into the staging area as loaded (their registers are free again before the softmax)
+    // Value rows into the staging area as loaded (their registers are free again before the softmax). Rows
+    // 16..31 swap neighbouring 32-byte blocks, so that the lanes of different kq read from different banks.
 #pragma unroll
-    for (int j = 0; j < 8; j++) *reinterpret_cast<u32x4_t*>(&T[4 * j + kq][8 * col]) = wt.Vr[j];
+    for (int j = 0; j < 8; j++) *reinterpret_cast<u32x4_t*>(&T[4 * j + kq][8 * (col ^ (j >= 4 ? 2 : 0))]) = wt.Vr[j];
     float x[8], p[8];
 #pragma unroll
     for (int m = 0; m < 2; m++)
@@ -435,7 +436,7 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
     for (int m = 0; m < 8; m++) {
       half8_t Avm;
 #pragma unroll
-      for (int e = 0; e < 8; e++) Avm[e] = __builtin_bit_cast(half_t, T[8 * kq + e][16 * m + col]);
+      for (int e = 0; e < 8; e++) Avm[e] = __builtin_bit_cast(half_t, T[8 * kq + e][16 * (m ^ (kq >> 1)) + col]);
       float4_t t = mfma16(Avm, PB, float4_t{0, 0, 0, 0});
       if constexpr (VB == 3) {   // the final 7/3 step factor of channels 10 / 21 applies to codes only
 #pragma unroll

@@ -25,7 +25,7 @@ def declared_functions():
 
 def test_every_declared_symbol_is_exported(kv):
     names = declared_functions()
-    assert {"kvmix_quantize_pack", "kvmix_append", "kvmix_decode_attn", "kvmix_dequant", "kvmix_cache_bytes",
+    assert {"kvmix_quantize_pack", "kvmix_append", "kvmix_decode_attn", "kvmix_decode_step", "kvmix_dequant", "kvmix_cache_bytes",
             "kvmix_workspace_bytes", "kvmix_version", "kvmix_strerror", "kvmix_last_hip_error"} <= set(names)
     L = kv.lib()
     for n in names:
@@ -73,6 +73,7 @@ def test_validation_rejects_before_launch(kv, shape_args, cfg_args, status):
     assert L.kvmix_decode_attn(C.byref(sh), C.byref(cfg), dummy, dummy, C.c_float(0.0), dummy, None, 0, 0, None) == status
     assert L.kvmix_quantize_pack(C.byref(sh), C.byref(cfg), dummy, dummy, 128, 128, 128, 32, 0, dummy, None) == status
     assert L.kvmix_append(C.byref(sh), C.byref(cfg), dummy, dummy, dummy, None) == status
+    assert L.kvmix_decode_step(C.byref(sh), C.byref(cfg), dummy, dummy, dummy, dummy, C.c_float(0.0), dummy, None, 0, 0, None) == status
 
 
 def test_null_and_alignment(kv):
@@ -82,3 +83,24 @@ def test_null_and_alignment(kv):
     assert L.kvmix_decode_attn(None, C.byref(cfg), None, None, C.c_float(0.0), None, None, 0, 0, None) == -1
     odd = C.c_void_p(4104)
     assert L.kvmix_decode_attn(C.byref(sh), C.byref(cfg), odd, None, C.c_float(0.0), C.c_void_p(4096), None, 0, 0, None) == -5
+
+
+def test_decode_step_checks_its_cache_on_the_host(kv):
+    """Host-side rejections of the fused step: nothing is launched, the counters stay as they were."""
+    import ctypes as C
+    from paper_2506_08018_amd.binding import _CacheStruct
+    L = kv.lib()
+    sh, cfg = kv.Shape(1, 4, 4), kv.LayerCfg(2, 2, 32)
+    a = C.c_void_p(4096)
+    full = _CacheStruct(4096, 4096, 4096, 64, 64, 0, 64, 0)          # window ring already full
+    assert L.kvmix_decode_step(C.byref(sh), C.byref(cfg), a, a, a, C.byref(full), C.c_float(0.0), a, None, 0, 0, None) == -4
+    assert (full.n_q, full.n_w, full.w0) == (0, 64, 0)
+    small = _CacheStruct(4096, 4096, 4096, 64, 32, 0, 5, 0)          # ring smaller than window + 32
+    assert L.kvmix_decode_step(C.byref(sh), C.byref(cfg), a, a, a, C.byref(small), C.c_float(0.0), a, None, 0, 0, None) == -4
+    nowin = _CacheStruct(4096, None, None, 64, 64, 0, 5, 0)
+    assert L.kvmix_decode_step(C.byref(sh), C.byref(cfg), a, a, a, C.byref(nowin), C.c_float(0.0), a, None, 0, 0, None) == -1
+    assert L.kvmix_decode_step(C.byref(sh), C.byref(cfg), None, a, a, C.byref(small), C.c_float(0.0), a, None, 0, 0, None) == -1
+    odd = C.c_void_p(4104)
+    ok = _CacheStruct(4096, 4096, 4096, 64, 64, 0, 5, 0)
+    assert L.kvmix_decode_step(C.byref(sh), C.byref(cfg), odd, a, a, C.byref(ok), C.c_float(0.0), a, None, 0, 0, None) == -5
+    assert ok.n_w == 5
