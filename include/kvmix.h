@@ -131,7 +131,7 @@ int kvmix_workspace_bytes(const kvmix_shape* shape, int T_max, size_t* bytes);
  * of 8). Per group: mn/mx by fp16 comparison; s = fp16((mx - mn) / qmax) with fp32
  * arithmetic; code = clamp(rint((x - mn) / s_i), 0, qmax_i) in fp32 with round-half-even,
  * where for 3 bit the in-group elements 10 and 21 use qmax_i = 3 and s_i = (s*7)/3;
- * a zero scale gives all-zero codes; the stored zero-point is mn (-0 stored as +0).
+ * a zero scale gives all-zero codes and is stored as +0; the stored zero-point is mn (-0 stored as +0).
  * Does not touch n_q / n_w (the caller sets cache->n_q). Inputs must be finite. */
 int kvmix_quantize_pack(const kvmix_shape* shape, const kvmix_layer_cfg* cfg,
                         const uint16_t* k_fp16, const uint16_t* v_fp16,

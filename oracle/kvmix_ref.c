@@ -110,6 +110,7 @@ void kvmix_ref_quantize_group(const uint16_t* x, int bits, uint8_t* code, uint16
   }
   if (mn == 0.0f) mn = 0.0f * 0.0f;                 /* -0 -> +0 */
   float range = mx - mn;                            /* step 1: s = (max - min) / q_max */
+  if (range == 0.0f) range = 0.0f * 0.0f;           /* a zero-range group stores scale +0 whatever the signs of its zeros */
   float s32 = range / (float)qmax_of(bits);
   *scale_h = f2h(s32);
   *zero_h = f2h(mn);                                /* exact: mn is an fp16 value */

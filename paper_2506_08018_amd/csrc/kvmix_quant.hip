@@ -12,8 +12,6 @@ namespace kvmix {
 
 namespace {
 
-constexpr int kRow = kD + 8;  // LDS row pitch in fp16 elements (272 B) to spread banks
-
 template <int BITS>
 __device__ __forceinline__ float step_of(float s, int i) {
   if (BITS == 3 && (i == 10 || i == 21)) return (s * 7.0f) / 3.0f;  // same range over q_max = 3
@@ -26,142 +24,245 @@ __device__ __forceinline__ int qmax_of(int i) {
   return (1 << BITS) - 1;
 }
 
-// One group of 32 values (already in registers as fp32, exact images of fp16 inputs).
+// value of lane (l ^ 1) / (l ^ 2) of each quad
+__device__ __forceinline__ uint32_t quad_x1(uint32_t v) { return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xf, 0xf, false); }
+__device__ __forceinline__ uint32_t quad_x2(uint32_t v) { return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xf, 0xf, false); }
+
+// Scale, minimum and the two reciprocal steps of one group from its extremes (fp32 images of fp16 values).
+struct GroupParams { float mn, s, inv, inv2; uint16_t scale_h, zero_h; };
 template <int BITS>
-__device__ __forceinline__ void quantize_group(const float (&x)[32], uint8_t (&code)[32], uint16_t& scale_h, uint16_t& zero_h) {
-  float mn = x[0], mx = x[0];
-#pragma unroll
-  for (int i = 1; i < 32; i++) {
-    mn = x[i] < mn ? x[i] : mn;
-    mx = x[i] > mx ? x[i] : mx;
-  }
+__device__ __forceinline__ GroupParams group_params(float mn, float mx) {
+  GroupParams g;
   if (mn == 0.0f) mn = 0.0f;                      // -0 -> +0
-  const float range = mx - mn;
+  float range = mx - mn;
+  if (range == 0.0f) range = 0.0f;                // a zero-range group stores scale +0 whatever the signs of its zeros
   const float s32 = range / (float)((1 << BITS) - 1);
   const half_t sh = (half_t)s32;                  // round-to-nearest-even
-  const float s = (float)sh;
-  scale_h = __builtin_bit_cast(uint16_t, sh);
-  zero_h = __builtin_bit_cast(uint16_t, (half_t)mn);
+  g.mn = mn;
+  g.s = (float)sh;
+  g.scale_h = __builtin_bit_cast(uint16_t, sh);
+  g.zero_h = __builtin_bit_cast(uint16_t, (half_t)mn);
+  // reciprocal steps (0 for a zero scale: every product, hence every code, is then 0)
+  g.inv = g.s != 0.0f ? 1.0f / g.s : 0.0f;
+  g.inv2 = g.s != 0.0f ? 1.0f / step_of<BITS>(g.s, 10) : 0.0f;   // the step of the two 2-bit elements of a 3-bit group
+  return g;
+}
+
+// code = clamp(rint((x - mn) / s_i)) with the IEEE quotient. The quotient itself is only needed when it lies
+// next to a rounding boundary: (x - mn) * (1 / s_i) is within 3 * 2^-24 relative of it (quotients stay below
+// 16, i.e. within 3e-6 absolute), so whenever that product is farther than 1e-5 from k + 1/2 both round to the
+// same integer. quantize_fast reports the near cases; the caller redoes a small batch of elements with
+// quantize_exact when any of them was near (rare). x >= mn always, so only the upper clip can act.
+// i: index of the element inside its group.
+template <int BITS>
+__device__ __forceinline__ float quantize_fast(float x, const GroupParams& g, int i, bool& near) {
+  const bool two_bit = BITS == 3 && (i == 10 || i == 21);
+  const float t = (x - g.mn) * (two_bit ? g.inv2 : g.inv);
+  const float r = __builtin_rintf(t);
+  near |= __builtin_fabsf(t - r) > 0.49999f;
+  return fminf(r, (float)qmax_of<BITS>(i));
+}
+template <int BITS>
+__device__ __forceinline__ float quantize_exact(float x, const GroupParams& g, int i) {
+  if (g.s == 0.0f) return 0.0f;
+  const float r = __builtin_rintf((x - g.mn) / step_of<BITS>(g.s, i));
+  return fminf(fmaxf(r, 0.0f), (float)qmax_of<BITS>(i));
+}
+
+__device__ __forceinline__ float half_lo(uint32_t w) { return (float)__builtin_bit_cast(half_t, (uint16_t)(w & 0xffffu)); }
+__device__ __forceinline__ float half_hi(uint32_t w) { return (float)__builtin_bit_cast(half_t, (uint16_t)(w >> 16)); }
+__device__ __forceinline__ half2_t as_half2(uint32_t w) { return __builtin_bit_cast(half2_t, w); }
+
+// Number of 32-bit word accumulators a lane fills for one code section before the lanes of its quad are
+// combined: words i = 0..15 of its (kq, j) column group; 4-bit sections have two chunks.
+template <int BITS> constexpr int acc_words() { return BITS == 4 ? 32 : 16; }
+
+// Final step shared by both waves: `w` holds, in every lane of a quad (q = lane & 3), the complete words
+// i = 0..15 (per chunk) of column group (kq, j); lane q stores the words i = 4q .. 4q+3. `hi` (3-bit only)
+// holds the high-plane words, complete in both lanes j and j^1; the even-j lanes store them.
+template <int BITS>
+__device__ __forceinline__ void store_words(uint32_t* sec, const uint32_t (&w)[acc_words<BITS>()], const uint32_t (&hi)[16],
+                                            int kq, int j, int q) {
+  constexpr int kChunks = BITS == 4 ? 2 : 1;
 #pragma unroll
-  for (int i = 0; i < 32; i++) {
-    float r = 0.0f;
-    if (s != 0.0f) {
-      const float t = (x[i] - mn) / step_of<BITS>(s, i);
-      r = __builtin_rintf(t);
-      const float hi = (float)qmax_of<BITS>(i);
-      r = r < 0.0f ? 0.0f : r;
-      r = r > hi ? hi : r;
+  for (int c = 0; c < kChunks; c++)
+#pragma unroll
+    for (int n = 0; n < 4; n++) {
+      const uint32_t v = q == 0 ? w[16 * c + n] : q == 1 ? w[16 * c + 4 + n] : q == 2 ? w[16 * c + 8 + n] : w[16 * c + 12 + n];
+      sec[256 * c + 4 * (16 * kq + 4 * q + n) + j] = v;
     }
-    code[i] = (uint8_t)r;
+  if constexpr (BITS == 3) {
+    if ((j & 1) == 0) {
+#pragma unroll
+      for (int n = 0; n < 4; n++) {
+        const uint32_t v = q == 0 ? hi[n] : q == 1 ? hi[4 + n] : q == 2 ? hi[8 + n] : hi[12 + n];
+        sec[256 + 2 * (16 * kq + 4 * q + n) + (j >> 1)] = v;
+      }
+    }
   }
 }
 
-// Assemble and store the words of one tile from the code bytes in LDS.
-template <int BITS, bool IS_VALUE>
-__device__ __forceinline__ void pack_tile(const uint8_t* cs /*[32][128]*/, uint32_t* dst, int tid, int nthreads) {
-  constexpr int kLoWords = (BITS == 4) ? 512 : 256;
-  for (int w = tid; w < kLoWords; w += nthreads) {
-    const int chunk = w >> 8, rem = w & 255, l = rem >> 2, j = rem & 3;
-    uint32_t val = 0;
+// One workgroup of two waves quantizes and packs one (unit, 32-token tile) entirely in registers: wave 0
+// the Key tile, wave 1 the Value tile. A lane owns what ends up in the same words: lane = 16*kq + 4*j + q.
+//   Key wave:   q = ks; channels d0 = 32*ks + 8*kq + 2*j and d0 + 1 over the 32 tokens (two groups); a word
+//               (l = 16*kq + i, j) gets its fields of slot ks + 4*m from this lane, the other ks from the quad.
+//   Value wave: q = g;  tokens 8*kq + 2*j and + 1, channels 32*g .. 32*g + 31 (two groups); a word gets its
+//               fields of slots 2*g, 2*g + 1 from this lane, the other blocks from the quad.
+// The lanes of a quad OR their partial words together (DPP), the 1-bit plane of 3-bit codes also across the
+// two j of a word; each lane then stores a quarter of the words. No LDS.
+template <int KB, int VB>
+__global__ __launch_bounds__(128) void quantize_pack_kernel(QuantArgs a) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int kq = lane >> 4, j = (lane >> 2) & 3, q = lane & 3;
+  const int tile_in = blockIdx.x, u = blockIdx.y;
+  const int b = u / a.Hkv, jh = u % a.Hkv;
+  uint32_t* rec = a.packed + ((size_t)u * a.tiles_cap + (size_t)(a.tile0 + tile_in)) * record_words(KB, VB);
+  uint32_t hi[16];
+#pragma unroll
+  for (int i = 0; i < 16; i++) hi[i] = 0;
+
+  if (wave == 0) {
+    const uint16_t* kin = a.k + b * a.k_unit_b + jh * a.k_unit_h + (int64_t)tile_in * kTile * a.k_tok;
+    const int d0 = 32 * q + 8 * kq + 2 * j;
+    uint32_t xw[kTile];                              // (x[tau][d0], x[tau][d0 + 1])
+#pragma unroll
+    for (int t = 0; t < kTile; t++) xw[t] = *reinterpret_cast<const uint32_t*>(kin + (int64_t)t * a.k_tok + d0);
+    half2_t mn2 = as_half2(xw[0]), mx2 = mn2;
+#pragma unroll
+    for (int t = 1; t < kTile; t++) {
+      mn2 = __builtin_elementwise_min(mn2, as_half2(xw[t]));
+      mx2 = __builtin_elementwise_max(mx2, as_half2(xw[t]));
+    }
+    const GroupParams g0 = group_params<KB>((float)mn2[0], (float)mx2[0]);
+    const GroupParams g1 = group_params<KB>((float)mn2[1], (float)mx2[1]);
+    // metadata word 4*(d0/2) + f: scale pair (f = 0), minimum pair (f = 1)
+    *reinterpret_cast<u32x2_t*>(rec + 4 * (d0 >> 1)) =
+        u32x2_t{(uint32_t)g0.scale_h | ((uint32_t)g1.scale_h << 16), (uint32_t)g0.zero_h | ((uint32_t)g1.zero_h << 16)};
+    uint32_t w[acc_words<KB>()];
+#pragma unroll
+    for (int i = 0; i < acc_words<KB>(); i++) w[i] = 0;
+#pragma unroll
+    for (int t0 = 0; t0 < kTile; t0 += 4) {
+      float r0[4], r1[4];
+      bool near = false;
+#pragma unroll
+      for (int n = 0; n < 4; n++) {
+        r0[n] = quantize_fast<KB>(half_lo(xw[t0 + n]), g0, t0 + n, near);
+        r1[n] = quantize_fast<KB>(half_hi(xw[t0 + n]), g1, t0 + n, near);
+      }
+      if (near) {
+#pragma unroll
+        for (int n = 0; n < 4; n++) {
+          r0[n] = quantize_exact<KB>(half_lo(xw[t0 + n]), g0, t0 + n);
+          r1[n] = quantize_exact<KB>(half_hi(xw[t0 + n]), g1, t0 + n);
+        }
+      }
+#pragma unroll
+      for (int n = 0; n < 4; n++) {
+      const int t = t0 + n;
+      const uint32_t c0 = (uint32_t)r0[n], c1 = (uint32_t)r1[n];
+      const int i = 4 * (t >> 3) + (t & 3), m = (t & 7) >> 2;       // word of the column group, token half
+      if constexpr (KB == 4) {
+        w[16 * m + i] |= (c0 | (c1 << 16)) << (4 * q);                // chunk m, field ks
+      } else {
+        w[i] |= ((c0 & 3u) | ((c1 & 3u) << 16)) << (2 * q + 8 * m);   // slot ks + 4*m
+        if constexpr (KB == 3) hi[i] |= ((c0 >> 2) | ((c1 >> 2) << 16)) << (8 * (j & 1) + 2 * q + m);
+      }
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < acc_words<KB>(); i++) { w[i] |= quad_x1(w[i]); w[i] |= quad_x2(w[i]); }
+    if constexpr (KB == 3) {
+#pragma unroll
+      for (int i = 0; i < 16; i++) { hi[i] |= quad_x1(hi[i]); hi[i] |= quad_x2(hi[i]); hi[i] |= (uint32_t)__shfl_xor((int)hi[i], 4); }
+    }
+    store_words<KB>(rec + kMetaWords, w, hi, kq, j, q);
+  } else {
+    const uint16_t* vin = a.v + b * a.v_unit_b + jh * a.v_unit_h + (int64_t)tile_in * kTile * a.v_tok;
+    const int tau0 = 8 * kq + 2 * j;
+    u32x4_t xr[2][4];                                // rows tau0, tau0 + 1: channels 32*q .. 32*q + 31
+#pragma unroll
+    for (int hh = 0; hh < 2; hh++)
+#pragma unroll
+      for (int c = 0; c < 4; c++) xr[hh][c] = *reinterpret_cast<const u32x4_t*>(vin + (int64_t)(tau0 + hh) * a.v_tok + 32 * q + 8 * c);
+    GroupParams gp[2];
 #pragma unroll
     for (int hh = 0; hh < 2; hh++) {
-      if (BITS == 4) {
+      half2_t mn2 = as_half2(xr[hh][0][0]), mx2 = mn2;
 #pragma unroll
-        for (int f = 0; f < 4; f++) {
-          int tau, d;
-          if (IS_VALUE) value_td(l, j, hh, 4 * chunk + f, tau, d); else key_td(l, j, hh, 4 * chunk + f, tau, d);
-          val |= (uint32_t)cs[tau * kD + d] << (16 * hh + 4 * f);
+      for (int e = 1; e < 16; e++) {
+        mn2 = __builtin_elementwise_min(mn2, as_half2(xr[hh][e >> 2][e & 3]));
+        mx2 = __builtin_elementwise_max(mx2, as_half2(xr[hh][e >> 2][e & 3]));
+      }
+      const float mn = fminf((float)mn2[0], (float)mn2[1]), mx = fmaxf((float)mx2[0], (float)mx2[1]);
+      gp[hh] = group_params<VB>(mn, mx);
+    }
+    // metadata word 4*(16*g + tau0/2) + f: scale pair (f = 2), minimum pair (f = 3)
+    *reinterpret_cast<u32x2_t*>(rec + 4 * (16 * q + (tau0 >> 1)) + 2) =
+        u32x2_t{(uint32_t)gp[0].scale_h | ((uint32_t)gp[1].scale_h << 16), (uint32_t)gp[0].zero_h | ((uint32_t)gp[1].zero_h << 16)};
+    // partial words with the lane-independent shifts first (fields of slot parity e/16 and token parity hh)
+    uint32_t pw[16], ph[16];
+#pragma unroll
+    for (int i = 0; i < 16; i++) { pw[i] = 0; ph[i] = 0; }
+#pragma unroll
+    for (int hh = 0; hh < 2; hh++)
+#pragma unroll
+      for (int e0 = 0; e0 < 32; e0 += 8) {
+      float r[8];
+      bool near = false;
+#pragma unroll
+      for (int n = 0; n < 8; n++) {
+        const uint32_t wv = xr[hh][e0 >> 3][n >> 1];
+        r[n] = quantize_fast<VB>((n & 1) ? half_hi(wv) : half_lo(wv), gp[hh], e0 + n, near);
+      }
+      if (near) {
+#pragma unroll
+        for (int n = 0; n < 8; n++) {
+          const uint32_t wv = xr[hh][e0 >> 3][n >> 1];
+          r[n] = quantize_exact<VB>((n & 1) ? half_hi(wv) : half_lo(wv), gp[hh], e0 + n);
         }
-      } else {
+      }
 #pragma unroll
-        for (int slot = 0; slot < 8; slot++) {
-          int tau, d;
-          if (IS_VALUE) value_td(l, j, hh, slot, tau, d); else key_td(l, j, hh, slot, tau, d);
-          val |= (uint32_t)(cs[tau * kD + d] & 3) << (16 * hh + 2 * slot);
+      for (int n = 0; n < 8; n++) {
+        const int e = e0 + n;
+        const uint32_t c = (uint32_t)r[n];
+        const int i = e & 15, sp = e >> 4;
+        if constexpr (VB == 4) {
+          pw[i] |= c << (16 * hh + 4 * sp);
+        } else {
+          pw[i] |= (c & 3u) << (16 * hh + 2 * sp);
+          if constexpr (VB == 3) ph[i] |= (c >> 2) << (16 * hh + 2 * sp);
+        }
+      }
+      }
+    uint32_t w[acc_words<VB>()];
+    if constexpr (VB == 4) {
+      // slot 2*g + sp: chunk g/2, field 2*(g%2) + sp; the chunk's words are complete after the pair (g, g^1)
+#pragma unroll
+      for (int i = 0; i < 16; i++) {
+        uint32_t v = pw[i] << (8 * (q & 1));
+        v |= quad_x1(v);
+        const uint32_t other = quad_x2(v);            // the other chunk's words, from lane g ^ 2
+        w[i] = (q & 2) ? other : v;                  // chunk 0
+        w[16 + i] = (q & 2) ? v : other;             // chunk 1
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 16; i++) {
+        w[i] = pw[i] << (4 * q);
+        w[i] |= quad_x1(w[i]); w[i] |= quad_x2(w[i]);
+      }
+      if constexpr (VB == 3) {
+        // high plane: bit 16*hh + 8*(j%2) + 2*(slot%4) + slot/4 with slot = 2*g + sp
+#pragma unroll
+        for (int i = 0; i < 16; i++) {
+          hi[i] = ph[i] << (8 * (j & 1) + 4 * (q & 1) + (q >> 1));
+          hi[i] |= quad_x1(hi[i]); hi[i] |= quad_x2(hi[i]); hi[i] |= (uint32_t)__shfl_xor((int)hi[i], 4);
         }
       }
     }
-    dst[w] = val;
+    store_words<VB>(rec + kMetaWords + tile_words(KB), w, hi, kq, j, q);
   }
-  if (BITS == 3) {
-    for (int w = tid; w < 128; w += nthreads) {
-      const int l = w >> 1, jp = w & 1;
-      uint32_t val = 0;
-#pragma unroll
-      for (int jj = 0; jj < 2; jj++)
-#pragma unroll
-        for (int hh = 0; hh < 2; hh++)
-#pragma unroll
-          for (int slot = 0; slot < 8; slot++) {
-            int tau, d;
-            if (IS_VALUE) value_td(l, 2 * jp + jj, hh, slot, tau, d); else key_td(l, 2 * jp + jj, hh, slot, tau, d);
-            val |= (uint32_t)(cs[tau * kD + d] >> 2) << (16 * hh + 8 * jj + 2 * (slot & 3) + (slot >> 2));
-          }
-      dst[256 + w] = val;
-    }
-  }
-}
-
-// One workgroup (256 threads) quantizes and packs the Key tile and the Value tile of one
-// (unit, 32-token tile): waves 0-1 own the 128 Key groups (one channel each), waves 2-3 the
-// 128 Value groups (one (token, 32-channel block) each).
-template <int KB, int VB>
-__global__ __launch_bounds__(256) void quantize_pack_kernel(QuantArgs a) {
-  __shared__ __attribute__((aligned(16))) uint16_t xs[2][kTile * kRow];
-  __shared__ __attribute__((aligned(16))) uint8_t cs[2][kTile * kD];
-  const int tid = threadIdx.x;
-  const int tile_in = blockIdx.x, u = blockIdx.y;
-  const int b = u / a.Hkv, jh = u % a.Hkv;
-  const uint16_t* kin = a.k + b * a.k_unit_b + jh * a.k_unit_h + (int64_t)tile_in * kTile * a.k_tok;
-  const uint16_t* vin = a.v + b * a.v_unit_b + jh * a.v_unit_h + (int64_t)tile_in * kTile * a.v_tok;
-
-  // stage the two fp16 tiles in LDS with 16-byte loads
-#pragma unroll
-  for (int p = 0; p < 2; p++) {
-    const int tau = (tid >> 4) + 16 * p, dc = (tid & 15) * 8;
-    const u32x4_t kv = *reinterpret_cast<const u32x4_t*>(kin + (int64_t)tau * a.k_tok + dc);
-    *reinterpret_cast<u32x4_t*>(&xs[0][tau * kRow + dc]) = kv;
-    const u32x4_t vv = *reinterpret_cast<const u32x4_t*>(vin + (int64_t)tau * a.v_tok + dc);
-    *reinterpret_cast<u32x4_t*>(&xs[1][tau * kRow + dc]) = vv;
-  }
-  __syncthreads();
-
-  uint32_t* rec = a.packed + ((size_t)u * a.tiles_cap + (size_t)(a.tile0 + tile_in)) * record_words(KB, VB);
-  uint16_t* meta = reinterpret_cast<uint16_t*>(rec);
-  float x[32];
-  uint8_t code[32];
-  uint16_t sh, zh;
-  if (tid < 128) {
-    const int d = tid;  // Key group: channel d, tokens 0..31
-#pragma unroll
-    for (int t = 0; t < 32; t++) x[t] = (float)__builtin_bit_cast(half_t, xs[0][t * kRow + d]);
-    quantize_group<KB>(x, code, sh, zh);
-#pragma unroll
-    for (int t = 0; t < 32; t++) cs[0][t * kD + d] = code[t];
-    meta[key_meta_half(d, 0)] = sh;
-    meta[key_meta_half(d, 1)] = zh;
-  } else {
-    const int tau = (tid - 128) & 31, g = (tid - 128) >> 5;  // Value group: token tau, channels 32g..32g+31
-#pragma unroll
-    for (int c = 0; c < 4; c++) {
-      const u32x4_t vv = *reinterpret_cast<const u32x4_t*>(&xs[1][tau * kRow + 32 * g + 8 * c]);
-      const uint16_t* e = reinterpret_cast<const uint16_t*>(&vv);
-#pragma unroll
-      for (int t = 0; t < 8; t++) x[8 * c + t] = (float)__builtin_bit_cast(half_t, e[t]);
-    }
-    quantize_group<VB>(x, code, sh, zh);
-#pragma unroll
-    for (int c = 0; c < 8; c++) {
-      uint32_t w = (uint32_t)code[4 * c] | ((uint32_t)code[4 * c + 1] << 8) | ((uint32_t)code[4 * c + 2] << 16) | ((uint32_t)code[4 * c + 3] << 24);
-      *reinterpret_cast<uint32_t*>(&cs[1][tau * kD + 32 * g + 4 * c]) = w;
-    }
-    meta[value_meta_half(tau, g, 0)] = sh;
-    meta[value_meta_half(tau, g, 1)] = zh;
-  }
-  __syncthreads();
-
-  pack_tile<KB, false>(cs[0], rec + kMetaWords, tid, 256);
-  pack_tile<VB, true>(cs[1], rec + kMetaWords + tile_words(KB), tid, 256);
 }
 
 // x = code * s_i + min, evaluated in fp32 (multiply, then add).
@@ -203,7 +304,7 @@ __global__ __launch_bounds__(128) void append_kernel(AppendArgs a) {
 
 template <int KB, int VB>
 hipError_t launch_qp(const QuantArgs& a, dim3 grid, hipStream_t s) {
-  quantize_pack_kernel<KB, VB><<<grid, 256, 0, s>>>(a);
+  quantize_pack_kernel<KB, VB><<<grid, 128, 0, s>>>(a);
   return hipGetLastError();
 }
 

@@ -95,6 +95,12 @@ def test_closed_forms(ref, bits):
     x[1] = 3.0
     _, s_b, z_b = ref.quantize_group(f16(x).view(np.uint16), bits)
     assert z_b == 0
+    # a zero-range group stores scale +0 and codes 0 whatever the signs and order of its zeros
+    for first in (0.0, -0.0):
+        x = np.where(np.arange(32) % 3 == 0, -0.0, 0.0)
+        x[0] = first
+        codes, s_b, z_b = ref.quantize_group(f16(x).view(np.uint16), bits)
+        assert s_b == 0 and z_b == 0 and not codes.any()
 
 
 @pytest.mark.parametrize("bits", BITS)
