@@ -199,3 +199,41 @@ def test_attn_error_returns():
         kv.decode_attn(kv.Shape(1, 6, 2), cfg, qt, gc, out, None)
     assert e.value.status == -4
     assert not out.any()
+
+
+@pytest.mark.parametrize("n_splits", [1, 4])
+def test_graph_replays_match_eager(n_splits):
+    """kvmix_decode_attn recorded into a HIP graph (it allocates nothing and clears its arrival counters in the
+    kernel): every replay, with eager work and synchronizations in between and a new query each time, gives the
+    eager result (to the last-bit freedom of the dynamic tile order) and matches the oracle."""
+    import torch
+    import paper_2506_08018_amd as kv
+    print(f"case graph replay splits={n_splits}", flush=True)
+    q, k, v, rc, gc, shape, cfg = make_pair(2, 8, 2, 32 * 21 + 9, 64, 3, 2, seed=950)
+    ws = torch.zeros(kv.workspace_bytes(shape, gc.T_cap), dtype=torch.uint8, device="cuda")
+    qt = torch.from_numpy(q).cuda()
+    out_g = torch.zeros_like(qt)
+    out_e = torch.zeros_like(qt)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        kv.decode_attn(shape, cfg, qt, gc, out_g, ws, n_splits=n_splits)      # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        kv.decode_attn(shape, cfg, qt, gc, out_g, ws, n_splits=n_splits)
+    rng = np.random.default_rng(3)
+    for rep in range(4):
+        qn = (q.astype(np.float32) * rng.uniform(0.6, 1.4)).astype(np.float16)
+        qt.copy_(torch.from_numpy(qn).cuda())                                   # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        kv.decode_attn(shape, cfg, qt, gc, out_e, ws, n_splits=n_splits)
+        torch.cuda.synchronize()
+        # waves claim tiles dynamically, so the summation order (and the last fp16 bit) may differ between launches
+        assert_attn_close(t16(out_g), t16(out_e), f"graph replay {rep} vs eager", tight=True)
+        st, want = rc.decode_attn(u16(qn))
+        assert_attn_close(t16(out_g), want, f"graph replay {rep}", tight=True)
+        assert not ws[: 4 * shape.units].any()

@@ -50,3 +50,45 @@ def test_full_size_sampled_units(name, n_sample):
             assert st == 0
             assert_attn_close(t16(out[b, j * G:(j + 1) * G]).reshape(1, G, 128), want, f"{name} unit {u} bits {kb}/{vb}", tight=True)
         del q, k, v, gc, out
+
+
+def test_full_size_fused_step_cfg2():
+    """kvmix_decode_step at the benchmark's shape and launch configuration (256 units, one workgroup each):
+    the appended token, the flush that follows 8 steps later and the attention over both, on sampled units."""
+    import torch
+    import paper_2506_08018_amd as kv
+    from oracle.kvmix_ref import RefCache
+    c = synth.CONFIGS["cfg2_llama2_7b"]
+    B, Hq, Hkv, T, W = c["B"], c["Hq"], c["Hkv"], c["T"], c["W"]
+    n_w0 = W + 24
+    n_q0 = T - 8 - n_w0
+    steps = 10
+    kb, vb = 3, 2
+    shape, cfg = kv.Shape(B, Hq, Hkv), kv.LayerCfg(kb, vb, W)
+    q, k, v = synth.gen_layer_torch("cuda", synth.BASE_SEED, 5, B, Hq, Hkv, n_q0 + n_w0 + steps)
+    gc = kv.LayerCache(shape, cfg, T + 64, W + 32)
+    kv.quantize_pack(shape, cfg, k[:, :, :n_q0], v[:, :, :n_q0], gc)
+    gc.set_window(k[:, :, n_q0:n_q0 + n_w0], v[:, :, n_q0:n_q0 + n_w0])
+    ws = torch.zeros(kv.workspace_bytes(shape, T + 64), dtype=torch.uint8, device="cuda")
+    units = np.random.default_rng(11).choice(B * Hkv, 3, replace=False)
+    refs = []
+    for u in units:
+        b, j = divmod(int(u), Hkv)
+        ku, vu = t16(k[b, j]).reshape(1, 1, -1, 128), t16(v[b, j]).reshape(1, 1, -1, 128)
+        rc = RefCache(1, 1, 1, kb, vb, W, T + 64, W + 32)
+        assert rc.quantize_pack(ku[:, :, :n_q0], vu[:, :, :n_q0]) == 0
+        rc.set_window(ku[:, :, n_q0:n_q0 + n_w0], vu[:, :, n_q0:n_q0 + n_w0])
+        refs.append((b, j, ku, vu, rc))
+    out = torch.zeros_like(q)
+    for s in range(steps):
+        print(f"case cfg2 fused step {s}", flush=True)
+        t = n_q0 + n_w0 + s
+        kv.decode_step(shape, cfg, k[:, :, t].contiguous(), v[:, :, t].contiguous(), q, gc, out, ws)
+        torch.cuda.synchronize()
+        for b, j, ku, vu, rc in refs:
+            assert rc.append(ku[:, :, t], vu[:, :, t]) == 0
+            assert (gc.n_q, gc.n_w, gc.w0) == (rc.n_q, rc.n_w, rc.w0)
+            st, want = rc.decode_attn(t16(q[b, j:j + 1]).reshape(1, 1, 128))
+            assert st == 0
+            assert_attn_close(t16(out[b, j:j + 1]).reshape(1, 1, 128), want, f"cfg2 fused step {s} unit {(b, j)}", tight=True)
+    assert gc.n_q == n_q0 + 32     # the flush happened inside the run
