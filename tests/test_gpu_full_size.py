@@ -9,7 +9,7 @@ from gpu_common import assert_attn_close, bits_of, t16, u16
 
 pytestmark = pytest.mark.gpu
 
-CASES = [("cfg2_llama2_7b", 16), ("cfg3_mistral_7b_gqa", 16), ("cfg4_llama3_8b_long", 4), ("cfg5_70b_stress", 16)]
+CASES = [("cfg2_llama2_7b", 16), ("cfg3_mistral_7b_gqa", 16), ("cfg4_llama3_8b_long", 8), ("cfg5_70b_stress", 16)]
 
 
 @pytest.mark.parametrize("name,n_sample", CASES)
