@@ -236,7 +236,7 @@ template <int G> struct __attribute__((aligned(16))) WaveLds {
   uint16_t zv[4][kTile];                   // Value zero-points [channel block][token]
 };
 
-template <int G> struct MergeLds {        // per-wave results (its own memory: a wave that is done never waits for the others)
+template <int G> struct __attribute__((aligned(16))) MergeLds {        // per-wave results (its own memory: a wave that is done never waits for the others)
   float o[waves_for(G)][G][kD];
   float m[waves_for(G)][G];
   float l[waves_for(G)][G];
@@ -788,6 +788,7 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
 #pragma unroll
   for (int m = 0; m < 8; m++) {
     const float sc = __builtin_ldexpf(1.0f, 24 - field_pos<VB>(m & 3));
+    float4_t o4;
 #pragma unroll
     for (int r = 0; r < 4; r++) {
       float v = acc[m][r] * sc;
@@ -796,9 +797,9 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
         if (dd == 10 || dd == 21) v *= (7.0f / 3.0f);
       }
       v += zsum[m >> 1];
-      v += ror8(v);
-      if (col < G) R.o[wave][col][16 * m + 4 * kq + r] = v;
+      o4[r] = v + ror8(v);
     }
+    if (col < G) *reinterpret_cast<float4_t*>(&R.o[wave][col][16 * m + 4 * kq]) = o4;   // channels 16m + 4kq .. +3
   }
   if (col < G && kq == 0) { R.m[wave][col] = mref; R.l[wave][col] = lsum; }
 
@@ -836,6 +837,9 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
         const bool has = lane < kWaves;
         const float mw = has ? R.m[has ? lane : 0][hh] : -INFINITY;
         const float lw = has ? R.l[has ? lane : 0][hh] : 0.0f;
+        float o0[kWaves], o1[kWaves];         // requested first: their latency overlaps the weight computation
+#pragma unroll
+        for (int w = 0; w < kWaves; w++) { o0[w] = R.o[w][hh][lane]; o1[w] = R.o[w][hh][lane + kWave]; }
         const float M = uniform_lane(row_max(mw), 0);
         const float fw = (mw == -INFINITY) ? 0.0f : fast_exp2(mw - M);
         const float Lsum = uniform_lane(row_sum(lw * fw), 0);
@@ -843,8 +847,8 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
 #pragma unroll
         for (int w = 0; w < kWaves; w++) {
           const float f = uniform_lane(fw, w);
-          O0 += R.o[w][hh][lane] * f;
-          O1 += R.o[w][hh][lane + kWave] * f;
+          O0 += o0[w] * f;
+          O1 += o1[w] * f;
         }
         const float inv = 1.0f / Lsum;
         outp[hh * kD + lane] = __builtin_bit_cast(uint16_t, (half_t)(O0 * inv));
