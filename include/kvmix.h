@@ -159,6 +159,15 @@ int kvmix_decode_attn(const kvmix_shape* shape, const kvmix_layer_cfg* cfg, cons
                       const kvmix_layer_cache* cache, float softmax_scale, uint16_t* out,
                       void* workspace, size_t workspace_bytes, int n_splits, void* stream);
 
+/* The same for n_tokens consecutive new tokens per sequence (chunked prefill, speculative decoding): exactly
+ * n_tokens calls of kvmix_append in a row, with as many flushes of 32 tokens as fall due. Element (b, j, i, d)
+ * of k_new / v_new is at b*batch_stride + j*head_stride + i*token_stride + d (strides in elements,
+ * token_stride >= 128). Capacity (T_cap, W_cap) is checked for the whole call before anything is launched. */
+int kvmix_append_tokens(const kvmix_shape* shape, const kvmix_layer_cfg* cfg,
+                        const uint16_t* k_new, const uint16_t* v_new,
+                        int64_t token_stride, int64_t head_stride, int64_t batch_stride, int n_tokens,
+                        kvmix_layer_cache* cache, void* stream);
+
 /* One decode step of a layer: kvmix_append followed by kvmix_decode_attn, same arguments and the same
  * result. Unless the append makes the window overflow (then the two calls are made as they are), the
  * append is done inside the attention launch: the workgroup that reads the window tile of the new slot

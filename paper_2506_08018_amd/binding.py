@@ -54,6 +54,8 @@ def lib():
         L.kvmix_quantize_pack.argtypes = [P, P, P, P, I64, I64, I64, I, I, P, P]
         L.kvmix_append.restype = I
         L.kvmix_append.argtypes = [P, P, P, P, P, P]
+        L.kvmix_append_tokens.restype = I
+        L.kvmix_append_tokens.argtypes = [P, P, P, P, I64, I64, I64, I, P, P]
         L.kvmix_decode_attn.restype = I
         L.kvmix_decode_attn.argtypes = [P, P, P, P, C.c_float, P, P, SZ, I, P]
         L.kvmix_decode_step.restype = I
@@ -151,6 +153,14 @@ def append(shape, cfg, k_new, v_new, cache):
     assert k_new.is_contiguous() and v_new.is_contiguous()
     _check(lib().kvmix_append(C.byref(shape), C.byref(cfg), k_new.data_ptr(), v_new.data_ptr(), C.byref(cache.c), _stream()),
            "kvmix_append")
+
+
+def append_tokens(shape, cfg, k_new, v_new, cache):
+    """k_new, v_new: fp16 CUDA tensors [B][Hkv][n][128] (last dim contiguous, any strides otherwise)."""
+    assert k_new.element_size() == 2 and k_new.stride(3) == 1 and v_new.stride() == k_new.stride() and v_new.shape == k_new.shape
+    st = lib().kvmix_append_tokens(C.byref(shape), C.byref(cfg), k_new.data_ptr(), v_new.data_ptr(), k_new.stride(2),
+                                   k_new.stride(1), k_new.stride(0), k_new.shape[2], C.byref(cache.c), _stream())
+    _check(st, "kvmix_append_tokens")
 
 
 def decode_attn(shape, cfg, q, cache, out, workspace=None, softmax_scale=0.0, n_splits=0, stream=None):

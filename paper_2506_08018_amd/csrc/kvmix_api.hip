@@ -135,41 +135,68 @@ int kvmix_quantize_pack(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const
   return e == hipSuccess ? KVMIX_OK : hip_fail(e);
 }
 
-int kvmix_append(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const uint16_t* k_new, const uint16_t* v_new,
-                 kvmix_layer_cache* c, void* stream) {
+int kvmix_append_tokens(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const uint16_t* k_new, const uint16_t* v_new,
+                        int64_t token_stride, int64_t head_stride, int64_t batch_stride, int n_tokens,
+                        kvmix_layer_cache* c, void* stream) {
   int st = check_shape_cfg(sh, cfg);
   if (st) return st;
   if (!k_new || !v_new) return KVMIX_ERR_NULL;
-  st = check_cache(cfg, c, cfg->k_bits != 16);
+  const bool packed = cfg->k_bits != 16;
+  st = check_cache(cfg, c, packed);
   if (st) return st;
-  if (c->n_w >= c->W_cap) return KVMIX_ERR_BAD_SHAPE;
-  const bool flush = cfg->k_bits != 16 && c->n_w + 1 == cfg->window + kTile;
-  if (cfg->k_bits != 16 && c->W_cap < cfg->window + kTile) return KVMIX_ERR_BAD_SHAPE;
-  if (flush && c->n_q + kTile > c->T_cap) return KVMIX_ERR_BAD_SHAPE;
+  if (n_tokens < 0) return KVMIX_ERR_BAD_SHAPE;
+  if (token_stride < kD || head_stride < 0 || batch_stride < 0) return KVMIX_ERR_ALIGN;
+  if (packed && c->W_cap < cfg->window + kTile) return KVMIX_ERR_BAD_SHAPE;
+  // dry run of the counters: nothing is launched unless everything fits
+  {
+    long long n_q = c->n_q, n_w = c->n_w;
+    if (n_w >= c->W_cap && n_tokens > 0) return KVMIX_ERR_BAD_SHAPE;
+    if (!packed) {
+      if (n_w + n_tokens > c->W_cap) return KVMIX_ERR_BAD_SHAPE;
+    } else {
+      if (n_w >= cfg->window + kTile && n_tokens > 0) return KVMIX_ERR_BAD_SHAPE;   // a flush is overdue: not a state this library leaves
+      const long long flushes = (n_w + n_tokens) >= cfg->window + kTile ? (n_w + n_tokens - cfg->window) / kTile : 0;
+      if (n_q + flushes * kTile > c->T_cap) return KVMIX_ERR_BAD_SHAPE;
+    }
+  }
   const int units = sh->B * sh->Hkv, W = c->W_cap;
-  AppendArgs ap{};
-  ap.k_new = k_new; ap.v_new = v_new; ap.k_win = c->k_win; ap.v_win = c->v_win;
-  ap.W_cap = W; ap.slot = (c->w0 + c->n_w) % W; ap.units = units;
-  hipError_t e = launch_append(ap, (hipStream_t)stream);
-  if (e != hipSuccess) return hip_fail(e);
-  c->n_w += 1;
-  if (flush) {
-    // the oldest 32 tokens are ring slots w0 .. w0+31; same quantizer, destination tile n_q/32
-    QuantArgs a{};
-    a.k = c->k_win + (size_t)c->w0 * kD;
-    a.v = c->v_win + (size_t)c->w0 * kD;
-    a.k_tok = kD; a.k_unit_b = (int64_t)sh->Hkv * W * kD; a.k_unit_h = (int64_t)W * kD;
-    a.v_tok = kD; a.v_unit_b = (int64_t)sh->Hkv * W * kD; a.v_unit_h = (int64_t)W * kD;
-    fill_quant_dst(a, c);
-    a.tile0 = c->n_q / kTile;
-    a.Hkv = sh->Hkv;
-    e = launch_quantize_pack(a, cfg->k_bits, cfg->v_bits, 1, units, (hipStream_t)stream);
+  int done = 0;
+  while (done < n_tokens) {
+    const int room = (packed ? cfg->window + kTile : W) - c->n_w;      // tokens until the window overflows
+    const int chunk = n_tokens - done < room ? n_tokens - done : room;
+    AppendArgs ap{};
+    ap.k_new = k_new + (int64_t)done * token_stride; ap.v_new = v_new + (int64_t)done * token_stride;
+    ap.tok = token_stride; ap.head = head_stride; ap.batch = batch_stride;
+    ap.k_win = c->k_win; ap.v_win = c->v_win;
+    ap.W_cap = W; ap.slot = (c->w0 + c->n_w) % W; ap.n = chunk; ap.units = units; ap.Hkv = sh->Hkv;
+    hipError_t e = launch_append(ap, (hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(e);
-    c->n_q += kTile;
-    c->n_w -= kTile;
-    c->w0 = (c->w0 + kTile) % W;
+    c->n_w += chunk;
+    done += chunk;
+    if (packed && c->n_w == cfg->window + kTile) {
+      // the oldest 32 tokens are ring slots w0 .. w0+31; same quantizer, destination tile n_q/32
+      QuantArgs a{};
+      a.k = c->k_win + (size_t)c->w0 * kD;
+      a.v = c->v_win + (size_t)c->w0 * kD;
+      a.k_tok = kD; a.k_unit_b = (int64_t)sh->Hkv * W * kD; a.k_unit_h = (int64_t)W * kD;
+      a.v_tok = kD; a.v_unit_b = (int64_t)sh->Hkv * W * kD; a.v_unit_h = (int64_t)W * kD;
+      fill_quant_dst(a, c);
+      a.tile0 = c->n_q / kTile;
+      a.Hkv = sh->Hkv;
+      e = launch_quantize_pack(a, cfg->k_bits, cfg->v_bits, 1, units, (hipStream_t)stream);
+      if (e != hipSuccess) return hip_fail(e);
+      c->n_q += kTile;
+      c->n_w -= kTile;
+      c->w0 = (c->w0 + kTile) % W;
+    }
   }
   return KVMIX_OK;
+}
+
+int kvmix_append(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const uint16_t* k_new, const uint16_t* v_new,
+                 kvmix_layer_cache* c, void* stream) {
+  if (!sh) return KVMIX_ERR_NULL;
+  return kvmix_append_tokens(sh, cfg, k_new, v_new, kD, kD, (int64_t)sh->Hkv * kD, 1, c, stream);
 }
 
 }  // extern "C"

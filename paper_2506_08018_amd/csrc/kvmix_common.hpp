@@ -75,9 +75,10 @@ struct DequantArgs {
 };
 
 struct AppendArgs {
-  const uint16_t* k_new; const uint16_t* v_new;
+  const uint16_t* k_new; const uint16_t* v_new;   // element (b, j, i, d) at b*batch + j*head + i*tok + d
+  int64_t tok, head, batch;
   uint16_t* k_win; uint16_t* v_win;
-  int W_cap; int slot; int units;
+  int W_cap; int slot; int n; int units; int Hkv;   // tokens i = 0..n-1 go to ring slots (slot + i) % W_cap
 };
 
 struct AttnArgs {

@@ -295,11 +295,13 @@ __global__ __launch_bounds__(256) void dequant_kernel(DequantArgs a) {
   }
 }
 
-// New token of every unit into ring slot `slot` of the two fp16 windows.
+// New tokens of every unit into consecutive ring slots of the two fp16 windows (one full row each).
 __global__ __launch_bounds__(128) void append_kernel(AppendArgs a) {
-  const int u = blockIdx.x, d = threadIdx.x;
-  a.k_win[((size_t)u * a.W_cap + a.slot) * kD + d] = a.k_new[(size_t)u * kD + d];
-  a.v_win[((size_t)u * a.W_cap + a.slot) * kD + d] = a.v_new[(size_t)u * kD + d];
+  const int u = blockIdx.x, i = blockIdx.y, d = threadIdx.x;
+  const int64_t src = (int64_t)(u / a.Hkv) * a.batch + (int64_t)(u % a.Hkv) * a.head + (int64_t)i * a.tok + d;
+  const size_t dst = ((size_t)u * a.W_cap + (a.slot + i) % a.W_cap) * kD + d;
+  a.k_win[dst] = a.k_new[src];
+  a.v_win[dst] = a.v_new[src];
 }
 
 template <int KB, int VB>
@@ -335,7 +337,8 @@ hipError_t launch_dequant(const DequantArgs& a, int units, hipStream_t s) {
 }
 
 hipError_t launch_append(const AppendArgs& a, hipStream_t s) {
-  append_kernel<<<a.units, 128, 0, s>>>(a);
+  if (a.n == 0 || a.units == 0) return hipSuccess;
+  append_kernel<<<dim3(a.units, a.n), 128, 0, s>>>(a);
   return hipGetLastError();
 }
 

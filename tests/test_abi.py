@@ -25,7 +25,7 @@ def declared_functions():
 
 def test_every_declared_symbol_is_exported(kv):
     names = declared_functions()
-    assert {"kvmix_quantize_pack", "kvmix_append", "kvmix_decode_attn", "kvmix_decode_step", "kvmix_dequant", "kvmix_cache_bytes",
+    assert {"kvmix_quantize_pack", "kvmix_append", "kvmix_append_tokens", "kvmix_decode_attn", "kvmix_decode_step", "kvmix_dequant", "kvmix_cache_bytes",
             "kvmix_workspace_bytes", "kvmix_version", "kvmix_strerror", "kvmix_last_hip_error"} <= set(names)
     L = kv.lib()
     for n in names:
@@ -74,6 +74,7 @@ def test_validation_rejects_before_launch(kv, shape_args, cfg_args, status):
     assert L.kvmix_quantize_pack(C.byref(sh), C.byref(cfg), dummy, dummy, 128, 128, 128, 32, 0, dummy, None) == status
     assert L.kvmix_append(C.byref(sh), C.byref(cfg), dummy, dummy, dummy, None) == status
     assert L.kvmix_decode_step(C.byref(sh), C.byref(cfg), dummy, dummy, dummy, dummy, C.c_float(0.0), dummy, None, 0, 0, None) == status
+    assert L.kvmix_append_tokens(C.byref(sh), C.byref(cfg), dummy, dummy, 128, 128, 512, 5, dummy, None) == status
 
 
 def test_null_and_alignment(kv):
@@ -104,3 +105,25 @@ def test_decode_step_checks_its_cache_on_the_host(kv):
     ok = _CacheStruct(4096, 4096, 4096, 64, 64, 0, 5, 0)
     assert L.kvmix_decode_step(C.byref(sh), C.byref(cfg), odd, a, a, C.byref(ok), C.c_float(0.0), a, None, 0, 0, None) == -5
     assert ok.n_w == 5
+
+
+def test_append_tokens_checks_capacity_for_the_whole_call(kv):
+    """A multi-token append that would overflow the packed capacity or the ring is refused as a whole:
+    nothing is launched, the counters stay as they were."""
+    import ctypes as C
+    from paper_2506_08018_amd.binding import _CacheStruct
+    L = kv.lib()
+    sh, cfg = kv.Shape(1, 4, 4), kv.LayerCfg(2, 2, 32)
+    a = C.c_void_p(4096)
+    c = _CacheStruct(4096, 4096, 4096, 64, 64, 32, 40, 0)            # room for one more tile of packed tokens
+    # 40 + 24 = 64 tokens: one flush, fits; 40 + 56 = 96: two flushes, does not
+    assert L.kvmix_append_tokens(C.byref(sh), C.byref(cfg), a, a, 128, 128, 512, 56, C.byref(c), None) == -4
+    assert (c.n_q, c.n_w, c.w0) == (32, 40, 0)
+    assert L.kvmix_append_tokens(C.byref(sh), C.byref(cfg), a, a, 128, 128, 512, -1, C.byref(c), None) == -4
+    assert L.kvmix_append_tokens(C.byref(sh), C.byref(cfg), a, a, 64, 128, 512, 1, C.byref(c), None) == -5
+    assert L.kvmix_append_tokens(C.byref(sh), C.byref(cfg), a, a, 128, 128, 512, 0, C.byref(c), None) == 0      # nothing to do
+    assert (c.n_q, c.n_w, c.w0) == (32, 40, 0)
+    c16 = _CacheStruct(None, 4096, 4096, 0, 64, 0, 60, 0)
+    cfg16 = kv.LayerCfg(16, 16, 0)
+    assert L.kvmix_append_tokens(C.byref(sh), C.byref(cfg16), a, a, 128, 128, 512, 5, C.byref(c16), None) == -4
+    assert c16.n_w == 60

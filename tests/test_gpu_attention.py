@@ -126,6 +126,37 @@ def test_append_and_flush_match_oracle(kb, vb, G):
     assert np.array_equal(bits_of(gc.v_win, np.uint16).reshape(rc.v_win.shape), rc.v_win)
 
 
+@pytest.mark.parametrize("kb,vb", [(2, 2), (3, 4), (16, 16)])
+def test_append_tokens_equals_single_appends(kb, vb):
+    """Chunks of new tokens (1, 7, 32, 45, 100 at a time, from a strided source) against the oracle's
+    token-by-token appends: counters, tile records and both windows bit for bit, attention at the end."""
+    import torch
+    import paper_2506_08018_amd as kv
+    print(f"case append_tokens kb={kb} vb={vb}", flush=True)
+    B, Hkv, G, W, T0 = 2, 2, 2, 32, 64 + 5
+    chunks = [1, 7, 32, 45, 100, 3]
+    total = sum(chunks)
+    q, k, v = synth.gen_layer_numpy(830, 0, B, Hkv * G, Hkv, T0 + total)
+    W_cap = 64 if kb != 16 else 320
+    _, _, _, rc, gc, shape, cfg = make_pair(B, Hkv * G, Hkv, T0, W, kb, vb, T_cap=320, W_cap=W_cap, q_k_v=(q, k[:, :, :T0], v[:, :, :T0]))
+    kt, vt = torch.from_numpy(k).cuda(), torch.from_numpy(v).cuda()
+    t = T0
+    for n in chunks:
+        for i in range(n):
+            assert rc.append(u16(k[:, :, t + i]), u16(v[:, :, t + i])) == 0
+        kv.append_tokens(shape, cfg, kt[:, :, t:t + n], vt[:, :, t:t + n], gc)      # a view: token stride 128, head stride T*128
+        t += n
+        assert (gc.n_q, gc.n_w, gc.w0) == (rc.n_q, rc.n_w, rc.w0)
+    torch.cuda.synchronize()
+    if kb != 16:
+        assert_cache_equal(rc, gc)
+    # window slots that hold live tokens must agree (slots past the live range keep older data on both sides)
+    assert np.array_equal(bits_of(gc.k_win, np.uint16).reshape(rc.k_win.shape), rc.k_win)
+    assert np.array_equal(bits_of(gc.v_win, np.uint16).reshape(rc.v_win.shape), rc.v_win)
+    st, want = rc.decode_attn(u16(q))
+    assert_attn_close(run_attn(gc, shape, cfg, q), want, "after chunked appends", tight=True)
+
+
 @pytest.mark.parametrize("kb,vb,G,n_splits", [(2, 2, 1, 0), (2, 3, 2, 3), (3, 4, 4, 1), (4, 2, 8, 2), (16, 16, 2, 0)])
 def test_decode_step_equals_append_then_attention(kb, vb, G, n_splits):
     """The fused step (append inside the attention launch, two launches + attention when the window overflows)
