@@ -6,8 +6,9 @@
  * benchmark's cpu_baseline leg. Nothing in the product path may call it.
  *
  * What it computes
- *   - the group-wise asymmetric quantizer of Sec. 3.2.2 (steps 1-4 and the q_max case
- *     equation for 3-bit blocks of 11), with Keys grouped per channel and Values per token
+ *   - the group-wise asymmetric quantizer of Sec. 3.2.2 at 1, 2, 3 and 4 bits (steps 1-4 and the q_max case
+ *     equation for 3-bit blocks of 11; with 1 bit the stored step is the group's range, which must be
+ *     representable in fp16), with Keys grouped per channel and Values per token
  *     (Sec. 3.2.1), group size 32 (Sec. 4.2);
  *   - the packed-cache encoding (bit positions documented in pos_key / pos_value, the tile
  *     record in the section "tile records" below);
@@ -140,12 +141,14 @@ static int words_per_tile(int bits) { return 128 * bits; } /* 32 x 128 codes, 32
 
 /* Bit fields of one code given the 16-byte column l (0..63) of its 1 KiB block, the word j
  * (0..3) inside the column, the 16-bit half hh of the word and its slot (0..7) inside the half.
+ *   1 bit: word 2l + j/2, bit 16hh + 8 (j%2) + 2 (slot%4) + slot/4  (32 codes per word, Sec. 3.2.2 step 4)
  *   2 bit: word 4l + j, bits [16hh + 2 slot, +2)
  *   4 bit: word 256 (slot/4) + 4l + j, bits [16hh + 4 (slot%4), +4)
  *   3 bit: code = lo + 4 hi; lo stored like a 2-bit tile, hi in a 1-bit plane after it:
  *          word 256 + 2l + j/2, bit 16hh + 8 (j%2) + 2 (slot%4) + slot/4 */
 static code_pos pos_from_slots(int bits, int l, int j, int hh, int slot) {
   code_pos p; p.hword = -1; p.hbit = 0;
+  if (bits == 1) { p.word = 2 * l + j / 2; p.bit = 16 * hh + 8 * (j % 2) + 2 * (slot % 4) + slot / 4; return p; }
   if (bits == 4) { p.word = 256 * (slot / 4) + 4 * l + j; p.bit = 16 * hh + 4 * (slot % 4); return p; }
   p.word = 4 * l + j; p.bit = 16 * hh + 2 * slot;
   if (bits == 3) { p.hword = 256 + 2 * l + j / 2; p.hbit = 16 * hh + 8 * (j % 2) + 2 * (slot % 4) + slot / 4; }
@@ -237,7 +240,7 @@ static int check_common(const ref_shape* sh, const ref_layer_cfg* cfg) {
   if (sh->D != D_HEAD || sh->B < 1 || sh->Hkv < 1 || sh->Hq < 1 || sh->Hq % sh->Hkv) return REF_ERR_BAD_SHAPE;
   int kb = cfg->k_bits, vb = cfg->v_bits;
   if (kb == 16 || vb == 16) return (kb == 16 && vb == 16) ? REF_OK : REF_ERR_BAD_BITS;
-  if (kb < 2 || kb > 4 || vb < 2 || vb > 4) return REF_ERR_BAD_BITS;
+  if (kb < 1 || kb > 4 || vb < 1 || vb > 4) return REF_ERR_BAD_BITS;
   return REF_OK;
 }
 

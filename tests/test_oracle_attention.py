@@ -55,7 +55,7 @@ def test_window_only_equals_library_attention(kb, vb, G):
     assert np.max(np.abs(h(out) - want)) <= np.maximum(np.abs(want), 2.0 ** -14).max() * 2.0 ** -11
 
 
-@pytest.mark.parametrize("kb,vb", [(2, 2), (3, 3), (4, 4), (2, 4), (3, 2)])
+@pytest.mark.parametrize("kb,vb", [(2, 2), (3, 3), (4, 4), (2, 4), (3, 2), (1, 1), (1, 3)])
 def test_dequant_is_within_half_step_of_inputs(kb, vb):
     """Cache-level round trip: every dequantized Key/Value is within s_i/2 of the fp16 input, with the
     Key step constant along tokens of a channel and the Value step constant along 32 channels of a token."""
@@ -81,7 +81,7 @@ def test_dequant_is_within_half_step_of_inputs(kb, vb):
     assert np.array_equal(vz, want)
 
 
-@pytest.mark.parametrize("kb,vb,G", [(2, 2, 1), (3, 4, 1), (4, 3, 4), (2, 4, 8)])
+@pytest.mark.parametrize("kb,vb,G", [(2, 2, 1), (3, 4, 1), (4, 3, 4), (2, 4, 8), (1, 2, 2), (4, 1, 1)])
 def test_attention_is_plain_attention_over_dequantized_cache(kb, vb, G):
     B, Hkv, T, W = 2, 2, 224, 32
     q, k, v, c = build_cache(B, Hkv * G, Hkv, T, W, kb, vb, seed=5)

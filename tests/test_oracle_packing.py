@@ -3,7 +3,7 @@ block of 11), bijectivity, and the pack/unpack identity."""
 import numpy as np
 import pytest
 
-BITS = [2, 3, 4]
+BITS = [1, 2, 3, 4]
 
 
 @pytest.mark.parametrize("bits", BITS)
@@ -12,7 +12,7 @@ def test_density(ref, bits):
     # (blocks of 11 = 10 x 3 bit + 1 x 2 bit = 32 bits; 11 + 11 + 10 elements)
     words = ref.words_per_tile(bits)
     n_groups = 128  # 32 x 128 codes / 32
-    assert words == n_groups * {2: 2, 3: 3, 4: 4}[bits]
+    assert words == n_groups * {1: 1, 2: 2, 3: 3, 4: 4}[bits]   # 1, 2, 4 bit: 32 / bit codes per word
     if bits in (2, 4):
         assert 32 * 128 // words == 32 // bits
     assert 10 * 3 + 2 == 32 and 11 + 11 + 10 == 32

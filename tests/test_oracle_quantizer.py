@@ -2,7 +2,7 @@
 import numpy as np
 import pytest
 
-BITS = [2, 3, 4]
+BITS = [1, 2, 3, 4]
 
 
 def f16(x):
@@ -142,10 +142,13 @@ def test_half_even_ties(ref):
 
 
 def test_extreme_range(ref):
-    x = np.zeros(32)
-    x[0] = -65504.0
-    x[1] = 65504.0
     for bits in BITS:
+        # the step (max - min) / q_max is stored as fp16: with one bit it is the range itself, which has to
+        # stay below the fp16 maximum (precondition of the 1-bit setting)
+        top = 65504.0 if bits > 1 else 32000.0
+        x = np.zeros(32)
+        x[0] = -top
+        x[1] = top
         codes, s, z, deq = run(ref, f16(x), bits)
         assert np.isfinite(s) and codes[0] == 0 and codes[1] == 2 ** bits - 1
         step = np.where(qmax_i(bits) == 2 ** bits - 1, s, s * 7 / 3)
