@@ -45,6 +45,8 @@
  *     Key code (tau, d):   ks = d/32, kq = (d%32)/8, j = (d%8)/2, hh = d%2,
  *                          m = (tau%8)/4, i = 4*(tau/8) + tau%4, slot = ks + 4*m
  *     Value code (tau, d): kq = tau/8, j = (tau%8)/2, hh = tau%2, i = d%16, slot = d/16
+ *     1-bit: word 2*l + j/2, bit 16*hh + 8*(j%2) + 2*(slot%4) + slot/4 (32 codes per word; the group's
+ *            range must be representable in fp16, it is the stored scale).
  *     2-bit: word 4*l + j, bits [16*hh + 2*slot, +2).
  *     4-bit: word 256*(slot/4) + 4*l + j, bits [16*hh + 4*(slot%4), +4).
  *     3-bit: code = lo + 4*hi. The 2-bit plane `lo` is stored exactly like a 2-bit section
@@ -74,7 +76,7 @@ extern "C" {
 typedef enum {
   KVMIX_OK = 0,
   KVMIX_ERR_NULL = -1,      /* a required pointer is NULL */
-  KVMIX_ERR_BAD_BITS = -2,  /* bits not in {2,3,4}, or 16 for one of K/V only */
+  KVMIX_ERR_BAD_BITS = -2,  /* bits not in {1,2,3,4}, or 16 for one of K/V only */
   KVMIX_ERR_BAD_GROUP = -3, /* group != 32 */
   KVMIX_ERR_BAD_SHAPE = -4, /* D != 128, Hq % Hkv, G not in {1,2,4,8}, counts not multiples of 32, capacity exceeded */
   KVMIX_ERR_ALIGN = -5,     /* a pointer is not 16-byte aligned or a stride is not a multiple of 8 elements */
@@ -93,7 +95,7 @@ typedef struct {
 
 /* One row of the per-layer bit table (Sec. 3.1 step 3, Sec. 4.2) plus the window length. */
 typedef struct {
-  int32_t k_bits; /* 2, 3, 4, or 16 (= keep the whole layer in the fp16 window) */
+  int32_t k_bits; /* 1, 2, 3, 4, or 16 (= keep the whole layer in the fp16 window) */
   int32_t v_bits; /* same set; 16 only together with k_bits == 16 */
   int32_t window; /* number of most recent tokens kept in fp16 (the RPC count), multiple of 32 */
 } kvmix_layer_cfg;

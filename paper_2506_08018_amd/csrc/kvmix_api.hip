@@ -28,7 +28,7 @@ int check_shape_cfg(const kvmix_shape* sh, const kvmix_layer_cfg* cfg) {
   const int kb = cfg->k_bits, vb = cfg->v_bits;
   if (kb == 16 || vb == 16) {
     if (kb != 16 || vb != 16) return KVMIX_ERR_BAD_BITS;
-  } else if (kb < 2 || kb > 4 || vb < 2 || vb > 4) {
+  } else if (kb < 1 || kb > 4 || vb < 1 || vb > 4) {
     return KVMIX_ERR_BAD_BITS;
   }
   if (cfg->window < 0 || cfg->window % kTile) return KVMIX_ERR_BAD_SHAPE;

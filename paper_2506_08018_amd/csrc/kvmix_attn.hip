@@ -93,7 +93,7 @@ __device__ __forceinline__ void wave_lds_fence() {
 // as they fit: the matrix core aligns the products of one dot product to their largest nominal
 // exponent (that of a subnormal is fixed) and truncates below its window, so a code sitting in the
 // lowest mantissa bits loses product bits (measured: ~1e-5 relative at position 0, exact from 6 up).
-template <int BITS> __device__ __forceinline__ constexpr int field_pos(int s) { return BITS == 4 ? 4 * (s & 1) + 2 : 2 * s + 2; }
+template <int BITS> __device__ __forceinline__ constexpr int field_pos(int s) { return BITS == 4 ? 4 * (s & 1) + 2 : BITS == 1 ? 2 * s + 4 : 2 * s + 2; }
 
 // ---- A operands from packed words. wa = word << 2, wb = word >> 6 (slots 0..3 / 4..7 of each half).
 // 2-bit plane (also the low plane of 3-bit): slot field from bits 2*slot to bits 2*(slot%4) + 2.
@@ -148,6 +148,10 @@ __device__ __forceinline__ u32x2_t buf_load8(rsrc_t r, uint32_t voff, uint32_t s
 
 // The lane's share of one packed tile as loaded (Raw) and prepared for unpacking (Codes).
 template <int BITS> struct Raw;
+template <> struct Raw<1> {     // the bit plane alone: 8 bytes per lane
+  u32x2_t h;
+  __device__ __forceinline__ void load(rsrc_t r, uint32_t soff, uint32_t, uint32_t l8) { h = buf_load8(r, l8, soff); }
+};
 template <> struct Raw<2> {
   u32x4_t w;
   __device__ __forceinline__ void load(rsrc_t r, uint32_t soff, uint32_t l16, uint32_t) { w = buf_load16(r, l16, soff); }
@@ -167,6 +171,11 @@ template <> struct Raw<4> {
   }
 };
 template <int BITS> struct Codes;
+template <> struct Codes<1> {
+  u32x2_t hs[4];
+  __device__ __forceinline__ explicit Codes(const Raw<1>& r) { shift_hi_plane(r.h, hs); }
+  __device__ __forceinline__ half8_t lo(int slot) const { return unpack1(hs, slot); }
+};
 template <> struct Codes<2> {
   u32x4_t wa, wb;
   __device__ __forceinline__ explicit Codes(const Raw<2>& r) : wa(r.w << 2), wb(r.w >> 6) {}
@@ -942,6 +951,13 @@ int attn_threads() { return waves_for(1) * kWave; }
 hipError_t launch_decode_attn(const AttnArgs& a, int k_bits, int v_bits, int G, int units, hipStream_t s) {
   const dim3 grid(a.n_splits, units);
   switch (k_bits * 10 + v_bits) {
+    case 11: return launch_g<1, 1>(a, G, grid, s);
+    case 12: return launch_g<1, 2>(a, G, grid, s);
+    case 13: return launch_g<1, 3>(a, G, grid, s);
+    case 14: return launch_g<1, 4>(a, G, grid, s);
+    case 21: return launch_g<2, 1>(a, G, grid, s);
+    case 31: return launch_g<3, 1>(a, G, grid, s);
+    case 41: return launch_g<4, 1>(a, G, grid, s);
     case 22: return launch_g<2, 2>(a, G, grid, s);
     case 23: return launch_g<2, 3>(a, G, grid, s);
     case 24: return launch_g<2, 4>(a, G, grid, s);

@@ -32,6 +32,11 @@ struct CodePos { int word, bit, hword, hbit; };
 __host__ __device__ inline CodePos pos_from_slots(int bits, int l, int j, int hh, int slot) {
   CodePos p;
   p.hword = -1; p.hbit = 0;
+  if (bits == 1) {
+    p.word = 2 * l + (j >> 1);
+    p.bit = 16 * hh + 8 * (j & 1) + 2 * (slot & 3) + (slot >> 2);
+    return p;
+  }
   if (bits == 4) {
     p.word = 256 * (slot >> 2) + 4 * l + j;
     p.bit = 16 * hh + 4 * (slot & 3);

@@ -74,7 +74,8 @@ __device__ __forceinline__ float half_hi(uint32_t w) { return (float)__builtin_b
 __device__ __forceinline__ half2_t as_half2(uint32_t w) { return __builtin_bit_cast(half2_t, w); }
 
 // Number of 32-bit word accumulators a lane fills for one code section before the lanes of its quad are
-// combined: words i = 0..15 of its (kq, j) column group; 4-bit sections have two chunks.
+// combined: words i = 0..15 of its (kq, j) column group; 4-bit sections have two chunks. 1-bit sections
+// consist of the bit plane alone (the `hi` words below, stored at the start of the section).
 template <int BITS> constexpr int acc_words() { return BITS == 4 ? 32 : 16; }
 
 // Final step shared by both waves: `w` holds, in every lane of a quad (q = lane & 3), the complete words
@@ -83,7 +84,8 @@ template <int BITS> constexpr int acc_words() { return BITS == 4 ? 32 : 16; }
 template <int BITS>
 __device__ __forceinline__ void store_words(uint32_t* sec, const uint32_t (&w)[acc_words<BITS>()], const uint32_t (&hi)[16],
                                             int kq, int j, int q) {
-  constexpr int kChunks = BITS == 4 ? 2 : 1;
+  constexpr int kChunks = BITS == 4 ? 2 : BITS == 1 ? 0 : 1;
+  constexpr int kPlane = BITS == 1 ? 0 : 256;     // first word of the 1-bit plane
 #pragma unroll
   for (int c = 0; c < kChunks; c++)
 #pragma unroll
@@ -91,12 +93,12 @@ __device__ __forceinline__ void store_words(uint32_t* sec, const uint32_t (&w)[a
       const uint32_t v = q == 0 ? w[16 * c + n] : q == 1 ? w[16 * c + 4 + n] : q == 2 ? w[16 * c + 8 + n] : w[16 * c + 12 + n];
       sec[256 * c + 4 * (16 * kq + 4 * q + n) + j] = v;
     }
-  if constexpr (BITS == 3) {
+  if constexpr (BITS == 3 || BITS == 1) {
     if ((j & 1) == 0) {
 #pragma unroll
       for (int n = 0; n < 4; n++) {
         const uint32_t v = q == 0 ? hi[n] : q == 1 ? hi[4 + n] : q == 2 ? hi[8 + n] : hi[12 + n];
-        sec[256 + 2 * (16 * kq + 4 * q + n) + (j >> 1)] = v;
+        sec[kPlane + 2 * (16 * kq + 4 * q + n) + (j >> 1)] = v;
       }
     }
   }
@@ -162,7 +164,9 @@ __global__ __launch_bounds__(128) void quantize_pack_kernel(QuantArgs a) {
       const int t = t0 + n;
       const uint32_t c0 = (uint32_t)r0[n], c1 = (uint32_t)r1[n];
       const int i = 4 * (t >> 3) + (t & 3), m = (t & 7) >> 2;       // word of the column group, token half
-      if constexpr (KB == 4) {
+      if constexpr (KB == 1) {
+        hi[i] |= (c0 | (c1 << 16)) << (8 * (j & 1) + 2 * q + m);      // the code is the plane's bit
+      } else if constexpr (KB == 4) {
         w[16 * m + i] |= (c0 | (c1 << 16)) << (4 * q);                // chunk m, field ks
       } else {
         w[i] |= ((c0 & 3u) | ((c1 & 3u) << 16)) << (2 * q + 8 * m);   // slot ks + 4*m
@@ -172,7 +176,7 @@ __global__ __launch_bounds__(128) void quantize_pack_kernel(QuantArgs a) {
     }
 #pragma unroll
     for (int i = 0; i < acc_words<KB>(); i++) { w[i] |= quad_x1(w[i]); w[i] |= quad_x2(w[i]); }
-    if constexpr (KB == 3) {
+    if constexpr (KB == 3 || KB == 1) {
 #pragma unroll
       for (int i = 0; i < 16; i++) { hi[i] |= quad_x1(hi[i]); hi[i] |= quad_x2(hi[i]); hi[i] |= (uint32_t)__shfl_xor((int)hi[i], 4); }
     }
@@ -227,7 +231,9 @@ __global__ __launch_bounds__(128) void quantize_pack_kernel(QuantArgs a) {
         const int e = e0 + n;
         const uint32_t c = (uint32_t)r[n];
         const int i = e & 15, sp = e >> 4;
-        if constexpr (VB == 4) {
+        if constexpr (VB == 1) {
+          ph[i] |= c << (16 * hh + 2 * sp);
+        } else if constexpr (VB == 4) {
           pw[i] |= c << (16 * hh + 4 * sp);
         } else {
           pw[i] |= (c & 3u) << (16 * hh + 2 * sp);
@@ -252,8 +258,8 @@ __global__ __launch_bounds__(128) void quantize_pack_kernel(QuantArgs a) {
         w[i] = pw[i] << (4 * q);
         w[i] |= quad_x1(w[i]); w[i] |= quad_x2(w[i]);
       }
-      if constexpr (VB == 3) {
-        // high plane: bit 16*hh + 8*(j%2) + 2*(slot%4) + slot/4 with slot = 2*g + sp
+      if constexpr (VB == 3 || VB == 1) {
+        // bit plane: bit 16*hh + 8*(j%2) + 2*(slot%4) + slot/4 with slot = 2*g + sp
 #pragma unroll
         for (int i = 0; i < 16; i++) {
           hi[i] = ph[i] << (8 * (j & 1) + 4 * (q & 1) + (q >> 1));
@@ -317,6 +323,13 @@ hipError_t launch_quantize_pack(const QuantArgs& a, int k_bits, int v_bits,
   if (n_tiles == 0 || units == 0) return hipSuccess;
   const dim3 grid(n_tiles, units);
   switch (k_bits * 10 + v_bits) {
+    case 11: return launch_qp<1, 1>(a, grid, s);
+    case 12: return launch_qp<1, 2>(a, grid, s);
+    case 13: return launch_qp<1, 3>(a, grid, s);
+    case 14: return launch_qp<1, 4>(a, grid, s);
+    case 21: return launch_qp<2, 1>(a, grid, s);
+    case 31: return launch_qp<3, 1>(a, grid, s);
+    case 41: return launch_qp<4, 1>(a, grid, s);
     case 22: return launch_qp<2, 2>(a, grid, s);
     case 23: return launch_qp<2, 3>(a, grid, s);
     case 24: return launch_qp<2, 4>(a, grid, s);
