@@ -7,14 +7,17 @@
 //   score[t][h] = sum_d code[t][d] * (q[h][d]*s[d])  +  sum_d q[h][d]*z[d]
 //   out[d][h]  += sum_t code[t][d] * (p[t][h]*s[t][g(d)])  +  sum_t p[t][h]*z[t][g(d)]
 // Both code sums are 16x16x32 fp16 MFMAs whose A operand is the packed word ANDed with a mask:
-// a 2/4-bit field left in place inside a zero fp16 pattern is the subnormal code * 2^(pos-24),
-// exact, and MFMA honours subnormal inputs. The scale factors ride in the B operand, split
+// a 1/2/4-bit field left in place inside a zero fp16 pattern is the subnormal code * 2^(pos-24),
+// exact, and MFMA honours subnormal inputs (3-bit codes are a 2-bit plane plus a 1-bit plane). The scale factors ride in the B operand, split
 // into an fp16 (hi, lo) pair held in two MFMA columns so that the products stay exact to
 // ~22 bits; the up-to-8 query heads of the group use columns 0..7 (hi) and 8..15 (lo).
-// The zero-point sums and the fp16 window are MFMAs on plain fp16 operands.
+// The fp16 window runs on MFMAs with plain fp16 operands; so do the zero-point sums for groups of
+// 4 or 8 query heads, while groups of 1 or 2 heads take them (and the softmax denominator) on the
+// vector unit, where they are cheaper than matrix instructions with mostly empty columns.
 //
 // Data movement. Every byte of a tile record is loaded from HBM once, by one lane (16 B of
-// metadata and 16 B of every 1 KiB of codes per lane), ahead of its use. The scale-folded
+// metadata and 16 B of every 1 KiB of codes per lane); a wave has one tile in flight while the
+// other waves of its SIMD compute. The scale-folded
 // B operands are computed cooperatively (each lane two values per head) and redistributed
 // through a wave-private LDS area, so no barrier is needed inside the main loop.
 // Softmax is online, per wave, with a lazily raised reference maximum; waves of a workgroup
@@ -29,7 +32,7 @@ namespace {
 
 // waves per workgroup: 3 per SIMD where the LDS exchange areas fit (register budget 512 / 3 per lane)
 constexpr int waves_for(int G) { return G == 8 ? 8 : 12; }
-constexpr int kDepth = 1;            // tiles in flight per wave beyond the one being processed: with 12 waves per CU deeper prefetch measured no faster
+constexpr int kDepth = 1;            // tiles a wave requests ahead; 2 and 3 measured no faster (the loop runs at the memory system's rate)
 constexpr float kRefMargin = 4.0f;   // reference maximum is raised to (tile max + margin), log2 units
 
 typedef float float2_t __attribute__((ext_vector_type(2)));
@@ -945,8 +948,6 @@ hipError_t launch_g(const AttnArgs& a, int G, dim3 grid, hipStream_t s) {
 }
 
 }  // namespace
-
-int attn_threads() { return waves_for(1) * kWave; }
 
 hipError_t launch_decode_attn(const AttnArgs& a, int k_bits, int v_bits, int G, int units, hipStream_t s) {
   const dim3 grid(a.n_splits, units);

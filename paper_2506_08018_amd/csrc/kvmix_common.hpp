@@ -107,6 +107,5 @@ hipError_t launch_quantize_pack(const QuantArgs& a, int k_bits, int v_bits,
 hipError_t launch_dequant(const DequantArgs& a, int units, hipStream_t s);
 hipError_t launch_append(const AppendArgs& a, hipStream_t s);
 hipError_t launch_decode_attn(const AttnArgs& a, int k_bits, int v_bits, int G, int units, hipStream_t s);
-int attn_threads();   // workgroup size of the attention kernel
 
 }  // namespace kvmix
