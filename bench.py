@@ -24,7 +24,7 @@ sys.path.insert(0, ROOT)
 import kvmix_synth as synth  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per attention launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/); None = not measured
+# HBM bytes per attention launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs; None = not measured
 MEASURED_TRAFFIC_BYTES = 127.27e6   # cfg2_llama2_7b, layer-weighted: 2.0 x FETCH_SIZE + 1.0 x WRITE_SIZE
 
 
@@ -115,8 +115,8 @@ def main():
                          "readings of the attention kernel can be scaled by what the same counters read for it")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs on one GPU only (every unit = (layer, batch, kv head) is independent; "
-                 "see DESIGN.md for how the path shards). Use --gpus 1.")
+        sys.exit("bench.py: this build runs on one GPU only (every unit = (layer, batch, kv head) is independent and "
+                 "would shard by kv head, batch or layer without any exchange). Use --gpus 1.")
 
     import torch
     import paper_2506_08018_amd as kv
