@@ -246,6 +246,7 @@ template <int G> struct __attribute__((aligned(16))) WaveLds {
   uint16_t bv[4][kRows + 1][kTile + 8];    // scale-folded probabilities [channel block][row][token]
   uint16_t pb[kRows + 1][kTile + 8];       // probabilities split hi/lo [row][token]
   uint16_t zv[4][kTile];                   // Value zero-points [channel block][token]
+  float pp[G][kTile];                      // softmax numerators [head][token] (groups of 4 or 8 heads)
 };
 
 template <int G> struct __attribute__((aligned(16))) MergeLds {        // per-wave results (its own memory: a wave that is done never waits for the others)
@@ -712,27 +713,42 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
       *reinterpret_cast<float4_t*>(&L.s[row][8 * kq + 4]) = float4_t{x[4], x[5], x[6], x[7]};
     }
     wave_lds_fence();
+    // The four lane groups g would all compute the same numerators; instead group g finishes those of the
+    // heads 4k + g only and hands them to the others through LDS, then every lane folds its own block's
+    // Value scales into all heads.
+    {
+      const int tp = lane & 15, g = lane >> 4;
+      float offs[G];
+#pragma unroll
+      for (int hh = 0; hh < G; hh++) offs[hh] = uniform_lane(off_col, hh);
+#pragma unroll
+      for (int k = 0; k < G / 4; k++) {
+        const int hh = 4 * k + g;                                  // differs between the lane groups
+        const float off = g == 0 ? offs[4 * k] : g == 1 ? offs[4 * k + 1] : g == 2 ? offs[4 * k + 2] : offs[4 * k + 3];
+        const float2_t sh = *reinterpret_cast<const float2_t*>(&L.s[hh][2 * tp]);
+        const float2_t sl = *reinterpret_cast<const float2_t*>(&L.s[G + hh][2 * tp]);
+        const float p0 = fast_exp2((sh[0] + sl[0]) * c_code + off);
+        const float p1 = fast_exp2((sh[1] + sl[1]) * c_code + off);
+        *reinterpret_cast<float2_t*>(&L.pp[hh][2 * tp]) = float2_t{p0, p1};
+        uint32_t hi, lo;
+        split_pair(p0, p1, hi, lo);                                // plain numerators: zero-point term and denominator
+        reinterpret_cast<uint32_t*>(&L.pb[hh][0])[tp] = hi;
+        reinterpret_cast<uint32_t*>(&L.pb[G + hh][0])[tp] = lo;
+      }
+      reinterpret_cast<uint32_t*>(&L.zv[0][0])[lane] = st.meta[3];
+    }
+    wave_lds_fence();
     {
       const int tp = lane & 15, g = lane >> 4;
       const float s0 = lo_half(st.meta[2]), s1 = hi_half(st.meta[2]);
 #pragma unroll
       for (int hh = 0; hh < G; hh++) {
-        const float off = uniform_lane(off_col, hh);
-        const float2_t sh = *reinterpret_cast<const float2_t*>(&L.s[hh][2 * tp]);
-        const float2_t sl = *reinterpret_cast<const float2_t*>(&L.s[G + hh][2 * tp]);
-        const float p0 = fast_exp2((sh[0] + sl[0]) * c_code + off);
-        const float p1 = fast_exp2((sh[1] + sl[1]) * c_code + off);
+        const float2_t pr = *reinterpret_cast<const float2_t*>(&L.pp[hh][2 * tp]);
         uint32_t hi, lo;
-        split_pair(p0 * s0, p1 * s1, hi, lo);
+        split_pair(pr[0] * s0, pr[1] * s1, hi, lo);
         reinterpret_cast<uint32_t*>(&L.bv[g][hh][0])[tp] = hi;
         reinterpret_cast<uint32_t*>(&L.bv[g][G + hh][0])[tp] = lo;
-        if ((hh & 3) == g) {   // plain probabilities (zero-point term), spread over the channel-block lanes
-          split_pair(p0, p1, hi, lo);
-          reinterpret_cast<uint32_t*>(&L.pb[hh][0])[tp] = hi;
-          reinterpret_cast<uint32_t*>(&L.pb[G + hh][0])[tp] = lo;
-        }
       }
-      reinterpret_cast<uint32_t*>(&L.zv[0][0])[lane] = st.meta[3];
     }
     wave_lds_fence();
     {
