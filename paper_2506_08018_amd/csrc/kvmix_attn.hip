@@ -315,8 +315,11 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
   // count it; its ring slot is masked like any slot past the end). One wave of the unit's first split adds
   // its term to the running softmax by hand and stores it into the window for the steps to come.
   const bool extra = a.new_slot >= 0 && sp == 0 && wave == kWaves - 1;   // wave-uniform
-  uint32_t knew_pair = 0;     // Key channels 2*lane, 2*lane+1 (requested now, the Value row when it is needed)
-  if (extra) knew_pair = reinterpret_cast<const uint32_t*>(a.k_new + (size_t)u * kD)[lane];
+  uint32_t knew_pair = 0, vnew_pair = 0;     // channels 2*lane, 2*lane+1 of the new Key / Value row, requested now
+  if (extra) {
+    knew_pair = reinterpret_cast<const uint32_t*>(a.k_new + (size_t)u * kD)[lane];
+    vnew_pair = reinterpret_cast<const uint32_t*>(a.v_new + (size_t)u * kD)[lane];
+  }
 
   constexpr uint32_t kRecBytes = (uint32_t)(record_words(KB, VB) * 4);
   const rsrc_t up = make_rsrc(reinterpret_cast<const char*>(a.packed) + (size_t)u * a.tiles_cap * kRecBytes, (uint32_t)a.tiles_cap * kRecBytes);
@@ -507,9 +510,16 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
   // ---- the token that is being appended (see above): score by packed dot products and a wave sum, then its
   // term of the running softmax in the accumulators' units (code domain: 2^(field position - 24))
   if (extra) {
-    u32x2_t vnew[8];               // Value channels 16*m + 4*kq .. +3
+    // the append itself: both rows are in registers, one 4-byte store per lane and row
+    reinterpret_cast<uint32_t*>(a.k_win_w + ((size_t)u * a.W_cap + a.new_slot) * kD)[lane] = knew_pair;
+    reinterpret_cast<uint32_t*>(a.v_win_w + ((size_t)u * a.W_cap + a.new_slot) * kD)[lane] = vnew_pair;
+    // the Value row in the order of the accumulators (channels 16*m + 4*kq .. +3 per lane), through 256 bytes of
+    // the exchange area that the next tile overwrites anyway
+    reinterpret_cast<uint32_t*>(&L.zv[0][0])[lane] = vnew_pair;
+    wave_lds_fence();
+    u32x2_t vnew[8];
 #pragma unroll
-    for (int m = 0; m < 8; m++) vnew[m] = *reinterpret_cast<const u32x2_t*>(a.v_new + (size_t)u * kD + 16 * m + 4 * kq);
+    for (int m = 0; m < 8; m++) vnew[m] = *reinterpret_cast<const u32x2_t*>(&L.zv[0][0] + 16 * m + 4 * kq);
     float s_lane = -INFINITY;      // the score of the lane's head, log2 domain
 #pragma unroll
     for (int hh = 0; hh < G; hh++) {
@@ -548,11 +558,7 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
         acc[m][r] += pn * v * unit;
       }
     }
-    // the append itself
-    for (int d = lane; d < kD; d += kWave) {
-      a.k_win_w[((size_t)u * a.W_cap + a.new_slot) * kD + d] = a.k_new[(size_t)u * kD + d];
-      a.v_win_w[((size_t)u * a.W_cap + a.new_slot) * kD + d] = a.v_new[(size_t)u * kD + d];
-    }
+    wave_lds_fence();   // the row has been read before the first tile's operands are written
   }
 
   auto process_small = [&](const Stage<KB, VB>& st) {
