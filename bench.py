@@ -25,7 +25,7 @@ import kvmix_synth as synth  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per attention launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs; None = not measured
-MEASURED_TRAFFIC_BYTES = 127.28e6   # cfg2_llama2_7b, layer-weighted: 2.0 x FETCH_SIZE + 1.0 x WRITE_SIZE
+MEASURED_TRAFFIC_BYTES = 127.44e6   # cfg2_llama2_7b, layer-weighted: 2.0 x FETCH_SIZE + 1.0 x WRITE_SIZE
 
 
 def algorithmic_bytes(units, n_q, n_w, kb, vb):
