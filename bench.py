@@ -92,12 +92,26 @@ def cpu_baseline(cfg, seed, kbits, vbits, target_s=12.0):
         reps += 1
     per_unit = t_attn / (reps * Bs * Hs)
     step_s = per_unit * total_units
+    # the same attention on one thread, one unit, a few seconds
+    kvmix_ref.set_num_threads(1)
+    rc1 = RefCache(1, G, 1, int(kbits[0]), int(vbits[0]), W, n_q, W + 32)
+    rc1.quantize_pack(u16(k[:1, :1, :n_q]), u16(v[:1, :1, :n_q]))
+    rc1.set_window(u16(k[:1, :1, n_q:]), u16(v[:1, :1, n_q:]))
+    t1, r1 = 0.0, 0
+    while t1 < 3.0 and r1 < 1000:
+        t0 = time.perf_counter()
+        rc1.decode_attn(u16(q[:1, :G]))
+        t1 += time.perf_counter() - t0
+        r1 += 1
+    kvmix_ref.set_num_threads(threads)
+    one_thread_step_s = t1 / r1 * total_units
     return {
         "value": B / step_s, "unit": "tokens/s", "cores": threads, "kind": "oracle",
         "sample": f"decode attention of {Bs * Hs} of {total_units} (layer,batch,kv-head) units (layer 0 bits "
                   f"K{int(kbits[0])}/V{int(vbits[0])}, context {T}), {reps} repetitions, {t_attn:.1f} s of CPU time, scaled "
                   f"linearly to all units; OpenMP over units",
         "quantize_pack_tokens_per_s": (reps * Bs * Hs * n_q) / t_qp,
+        "one_thread_value": B / one_thread_step_s,
     }
 
 

@@ -244,6 +244,15 @@ static int check_common(const ref_shape* sh, const ref_layer_cfg* cfg) {
   return REF_OK;
 }
 
+/* Number of OpenMP threads of the following calls (timing only; n < 1 is ignored). */
+void kvmix_ref_set_num_threads(int n) {
+#ifdef _OPENMP
+  if (n >= 1) omp_set_num_threads(n);
+#else
+  (void)n;
+#endif
+}
+
 int kvmix_ref_num_threads(void) {
 #ifdef _OPENMP
   return omp_get_max_threads();

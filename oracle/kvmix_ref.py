@@ -44,6 +44,8 @@ def lib():
         L.kvmix_ref_unpack_tile.restype = None
         L.kvmix_ref_unpack_tile.argtypes = [C.c_int, C.c_int, C.c_void_p, C.c_void_p]
         L.kvmix_ref_num_threads.restype = C.c_int
+        L.kvmix_ref_set_num_threads.restype = None
+        L.kvmix_ref_set_num_threads.argtypes = [C.c_int]
         L.kvmix_ref_record_words.restype = C.c_int
         L.kvmix_ref_record_words.argtypes = [C.c_int, C.c_int]
         L.kvmix_ref_quantize_pack.restype = C.c_int
@@ -61,6 +63,10 @@ def lib():
 
 def num_threads() -> int:
     return lib().kvmix_ref_num_threads()
+
+
+def set_num_threads(n: int) -> None:
+    lib().kvmix_ref_set_num_threads(int(n))
 
 
 def h2d(h: int) -> float:
