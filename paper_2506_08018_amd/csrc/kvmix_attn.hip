@@ -33,6 +33,7 @@ namespace {
 // waves per workgroup: 3 per SIMD where the LDS exchange areas fit (register budget 512 / 3 per lane)
 constexpr int waves_for(int G) { return G == 8 ? 8 : 12; }
 constexpr int kDepth = 1;            // tiles a wave requests ahead; 2 and 3 measured no faster (the loop runs at the memory system's rate)
+constexpr int kMergeBatch = 8;           // splits whose partials the merging workgroup requests together (one round trip)
 constexpr float kRefMargin = 4.0f;   // reference maximum is raised to (tile max + margin), log2 units
 
 typedef float float2_t __attribute__((ext_vector_type(2)));
@@ -929,27 +930,28 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
     const int hh = idx / kD, d = idx % kD;
     const float* base = a.part + ((size_t)u * a.n_splits * G + hh) * (kD + 2);
     const size_t stride = (size_t)G * (kD + 2);
-    // one pass, eight splits per round trip: the loads of a batch are issued together
+    // one pass, kMergeBatch splits per round trip: the loads of a batch are issued together
     float M = -INFINITY, Lsum = 0.0f, O = 0.0f;
-    for (int s0 = 0; s0 < a.n_splits; s0 += 8) {
-      float ms[8], ls[8], os[8];
+    for (int s0 = 0; s0 < a.n_splits; s0 += kMergeBatch) {
+      float ms[kMergeBatch], ls[kMergeBatch], os[kMergeBatch];
 #pragma unroll
-      for (int k = 0; k < 8; k++) {
-        const bool in = s0 + k < a.n_splits;
-        const float* pp = base + (size_t)(in ? s0 + k : s0) * stride;
-        ms[k] = ld_agent(pp);
-        ls[k] = ld_agent(pp + 1);
-        os[k] = ld_agent(pp + 2 + d);
-        if (!in) ms[k] = -INFINITY;
+      for (int k = 0; k < kMergeBatch; k++) {
+        ms[k] = -INFINITY; ls[k] = 0.0f; os[k] = 0.0f;
+        if (s0 + k < a.n_splits) {          // wave-uniform: no request for splits that do not exist
+          const float* pp = base + (size_t)(s0 + k) * stride;
+          ms[k] = ld_agent(pp);
+          ls[k] = ld_agent(pp + 1);
+          os[k] = ld_agent(pp + 2 + d);
+        }
       }
       float Mn = M;
 #pragma unroll
-      for (int k = 0; k < 8; k++) Mn = fmaxf(Mn, ms[k]);
+      for (int k = 0; k < kMergeBatch; k++) Mn = fmaxf(Mn, ms[k]);
       const float fold = (M == -INFINITY) ? 0.0f : fast_exp2(M - Mn);
       Lsum *= fold;
       O *= fold;
 #pragma unroll
-      for (int k = 0; k < 8; k++) {
+      for (int k = 0; k < kMergeBatch; k++) {
         const float f = (ms[k] == -INFINITY) ? 0.0f : fast_exp2(ms[k] - Mn);
         Lsum += ls[k] * f;
         O += os[k] * f;
