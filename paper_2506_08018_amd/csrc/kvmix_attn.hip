@@ -347,13 +347,18 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
   auto win_load = [&](int wi, WinTile& w) {
     const int slot0 = wi * kTile;
     const uint16_t* kw = a.k_win + ((size_t)u * a.W_cap + slot0) * kD;
-    const uint16_t* vw = a.v_win + ((size_t)u * a.W_cap + slot0) * kD;
 #pragma unroll
     for (int m = 0; m < 2; m++) {
       const int tau = 8 * (col >> 2) + 4 * m + (col & 3);   // row `col` of M-tile m
 #pragma unroll
       for (int ks = 0; ks < 4; ks++) w.Ak[m][ks] = *reinterpret_cast<const half8_t*>(kw + (size_t)tau * kD + 32 * ks + 8 * kq);
     }
+  };
+  // The Value rows are requested only when the Key rows have been consumed: fewer registers in flight (no
+  // spills in any variant) and a smaller first burst, so that the first packed tiles arrive earlier
+  // (measured 0.3-0.4 us per launch against requesting both at the start).
+  auto win_load_v = [&](int wi, WinTile& w) {
+    const uint16_t* vw = a.v_win + ((size_t)u * a.W_cap + wi * kTile) * kD;
 #pragma unroll
     for (int j = 0; j < 8; j++) w.Vr[j] = *reinterpret_cast<const u32x4_t*>(vw + (size_t)(4 * j + kq) * kD + 8 * col);
   };
@@ -433,6 +438,7 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
     for (int m = 0; m < 2; m++)
 #pragma unroll
       for (int ks = 0; ks < 4; ks++) S[m] = mfma16(Ak[m][ks], qB[ks], S[m]);
+    win_load_v(wi, wt);
     // Value rows into the staging area as loaded (their registers are free again before the softmax). Rows
     // 16..31 swap neighbouring 32-byte blocks, so that the lanes of different kq read from different banks.
 #pragma unroll
