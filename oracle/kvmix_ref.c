@@ -133,6 +133,31 @@ double kvmix_ref_dequant_elem(int code, int i, int bits, uint16_t scale_h, uint1
   return (double)code * (double)step_elem(bits, i, scale_h) + kvmix_ref_h2d(zero_h);
 }
 
+/* ------------------------------------------------------------------ the 3-bit word as the paper words it
+ * Sec. 3.2.2: the 32 codes of a 3-bit group as blocks of 11, each block in one 32-bit integer: the block's first
+ * ten elements as 3-bit fields (element j at bits [3j, 3j+3)) and its 11th element as a 2-bit field at bits
+ * [30, 32). A group of 32 is 11 + 11 + 10 elements, so three words, the third with bits 30-31 unused.
+ * The tile records below store the same 3 x 32 bits per group in another order (a 2-bit plane and a 1-bit
+ * plane); this form exists to tie that order to the paper's sentence (tests compare the two). */
+void kvmix_ref_pack_literal3(const uint8_t* code, uint32_t* words) {
+  for (int w = 0; w < 3; w++) {
+    words[w] = 0;
+    for (int j = 0; j < 11; j++) {
+      int i = 11 * w + j;
+      if (i >= GROUP) break;
+      if (j < 10) words[w] |= (uint32_t)(code[i] & 7u) << (3 * j);
+      else words[w] |= (uint32_t)(code[i] & 3u) << 30;
+    }
+  }
+}
+
+void kvmix_ref_unpack_literal3(const uint32_t* words, uint8_t* code) {
+  for (int i = 0; i < GROUP; i++) {
+    int w = i / 11, j = i % 11;
+    code[i] = (uint8_t)(j < 10 ? (words[w] >> (3 * j)) & 7u : (words[w] >> 30) & 3u);
+  }
+}
+
 /* ------------------------------------------------------------------ packed tile encoding */
 
 typedef struct { int word, bit, hword, hbit; } code_pos; /* hword < 0: no high plane */

@@ -43,6 +43,10 @@ def lib():
         L.kvmix_ref_pack_tile.argtypes = [C.c_int, C.c_int, C.c_void_p, C.c_void_p]
         L.kvmix_ref_unpack_tile.restype = None
         L.kvmix_ref_unpack_tile.argtypes = [C.c_int, C.c_int, C.c_void_p, C.c_void_p]
+        L.kvmix_ref_pack_literal3.restype = None
+        L.kvmix_ref_pack_literal3.argtypes = [C.c_void_p, C.c_void_p]
+        L.kvmix_ref_unpack_literal3.restype = None
+        L.kvmix_ref_unpack_literal3.argtypes = [C.c_void_p, C.c_void_p]
         L.kvmix_ref_num_threads.restype = C.c_int
         L.kvmix_ref_set_num_threads.restype = None
         L.kvmix_ref_set_num_threads.argtypes = [C.c_int]
@@ -115,6 +119,23 @@ def unpack_tile(which, bits, tile):
     assert tile.shape == (words_per_tile(bits),)
     codes = np.zeros((32, 128), np.uint8)
     lib().kvmix_ref_unpack_tile(int(which), int(bits), _ptr(tile), _ptr(codes))
+    return codes
+
+
+def pack_literal3(codes):
+    """32 codes of a 3-bit group -> the three 32-bit words of the paper's own wording (blocks of 11)."""
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    assert codes.shape == (32,)
+    words = np.zeros(3, np.uint32)
+    lib().kvmix_ref_pack_literal3(_ptr(codes), _ptr(words))
+    return words
+
+
+def unpack_literal3(words):
+    words = np.ascontiguousarray(words, dtype=np.uint32)
+    assert words.shape == (3,)
+    codes = np.zeros(32, np.uint8)
+    lib().kvmix_ref_unpack_literal3(_ptr(words), _ptr(codes))
     return codes
 
 

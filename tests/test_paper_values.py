@@ -41,5 +41,11 @@ def test_codes_per_word(ref):
     g = golden()
     for bits, name in ((1, "codes_per_word_1bit"), (2, "codes_per_word_2bit"), (4, "codes_per_word_4bit")):
         assert 32 * 128 // ref.words_per_tile(bits) == int(g[name])
-    # 3 bit: a group of 32 is two blocks of 11 and one of 10, three words in all
-    assert ref.words_per_tile(3) * 32 // (32 * 128) == 3 and 2 * int(g["codes_per_word_3bit"]) + 10 == 32
+    # 3 bit: the literal word of the oracle holds the paper's 11 codes (a 12th would not fit: 10 x 3 + 2 = 32 bits),
+    # and a group of 32 is two such blocks and one of 10, three words in all, also in the tile record's form
+    n = int(g["codes_per_word_3bit"])
+    codes = np.zeros(32, np.uint8)
+    codes[:n] = [7] * (n - 1) + [3]
+    w = ref.pack_literal3(codes)
+    assert w[0] == 0xFFFFFFFF and w[1] == 0 and w[2] == 0
+    assert ref.words_per_tile(3) * 32 // (32 * 128) == 3
