@@ -4,12 +4,12 @@
  * The library implements the two data-parallel parts of KVmix (arXiv 2506.08018):
  *   part 1  group-wise asymmetric min/max quantization of the KV cache at a layer's own
  *           Key / Value bit-width, with bit-packing into 32-bit words (paper Sec. 3.2.1,
- *           3.2.2 incl. the unnumbered q_max equation for the 3-bit "10 x 3 bit + 1 x 2 bit"
- *           block), applied to tokens that leave the full-precision recent window
+ *           3.2.2 incl. the unnumbered q_max equation for the 3-bit block of ten 3-bit and one
+ *           2-bit element), applied to tokens that leave the full-precision recent window
  *           (Recent Pivotal Context, Sec. 3.3, Fig. 4); and
- *   part 2  decode attention that dequantizes the packed codes on the fly while it
- *           multiplies ("fusion of dequantization and matrix-vector multiplication",
- *           Sec. 3.4 item 2), over [packed old tokens || fp16 recent window].
+ *   part 2  decode attention that dequantizes the packed codes inside the dot products and never
+ *           materializes an fp16 copy of the packed cache (Sec. 3.4 item 2), over
+ *           [packed old tokens || fp16 recent window].
  * The per-layer bit table (Sec. 3.1, Sec. 4.2) is an input.
  *
  * Conventions
@@ -61,13 +61,48 @@
  * Recent window (fp16, ring buffer of W_cap slots, W_cap % 32 == 0, W_cap >= window + 32)
  *   k_win, v_win : [units][W_cap][128]   (channel contiguous: appending a token writes one full row of each)
  *   The n_w valid tokens sit in slots (w0 + r) % W_cap, r = 0..n_w-1, oldest first;
- *   w0 % 32 == 0. Both windows must hold finite values in every slot (zero-fill at allocation).
+ *   w0 % 32 == 0. Both windows must hold finite values in every slot (zero-fill at allocation):
+ *   slots outside the n_w valid ones are masked by multiplying with zero, not skipped.
+ *
+ * Numeric preconditions (not checked on the device)
+ *   - all K / V / q inputs are finite (Sec. 3.2.2 defines the quantizer on real numbers only);
+ *   - 1-bit groups: max - min of a group must be <= 65504, because the stored fp16 scale is the range
+ *     itself (with 2-4 bits the scale (max - min)/q_max of finite fp16 inputs is always representable);
+ *   - attention folds q*scale products into fp16 matrix-core operands: |q[h][d]| * s[d] < 16384 for every
+ *     Key group scale s[d] and every Value scale times a softmax weight <= 1, i.e. s < 16384; both hold
+ *     for any cache whose values stay below ~10^4 in magnitude at |q| <= 8.
  */
 #ifndef KVMIX_H_
 #define KVMIX_H_
 
 #include <stddef.h>
 #include <stdint.h>
+
+/* ---- Reaching codes, scales and minima inside a tile record (the layout statement above as code).
+ * All indices are relative to the record's first 32-bit word (or first 16-bit half-word where said). */
+static inline int kvmix_record_words(int k_bits, int v_bits) { return 256 + 128 * k_bits + 128 * v_bits; }
+static inline int kvmix_key_codes_word(void) { return 256; }
+static inline int kvmix_value_codes_word(int k_bits) { return 256 + 128 * k_bits; }
+/* 16-bit half-word index of the fp16 scale (f = 0) / minimum (f = 1) of the Key group of channel d (0..127) */
+static inline int kvmix_key_meta_half(int d, int f) { return 2 * (4 * (d / 2) + f) + d % 2; }
+/* the same for the Value group of token tau (0..31), channel block g = d / 32 (0..3) */
+static inline int kvmix_value_meta_half(int tau, int g, int f) { return 2 * (4 * (16 * g + tau / 2) + 2 + f) + tau % 2; }
+/* Position of the code of (token tau, channel d) inside its code section: its low `bits` (2 for 3-bit codes)
+ * start at bit *bit of word *word; for 3-bit codes the third bit is bit *hbit of word *hword (else *hword = -1). */
+static inline void kvmix_code_position(int is_value, int bits, int tau, int d, int* word, int* bit, int* hword, int* hbit) {
+  int l, j, hh, slot;
+  if (!is_value) {
+    const int ks = d / 32, kq = (d % 32) / 8, m = (tau % 8) / 4, i = 4 * (tau / 8) + tau % 4;
+    l = 16 * kq + i; j = (d % 8) / 2; hh = d % 2; slot = ks + 4 * m;
+  } else {
+    l = 16 * (tau / 8) + d % 16; j = (tau % 8) / 2; hh = tau % 2; slot = d / 16;
+  }
+  *hword = -1; *hbit = 0;
+  if (bits == 1) { *word = 2 * l + j / 2; *bit = 16 * hh + 8 * (j % 2) + 2 * (slot % 4) + slot / 4; return; }
+  if (bits == 4) { *word = 256 * (slot / 4) + 4 * l + j; *bit = 16 * hh + 4 * (slot % 4); return; }
+  *word = 4 * l + j; *bit = 16 * hh + 2 * slot;
+  if (bits == 3) { *hword = 256 + 2 * l + j / 2; *hbit = 16 * hh + 8 * (j % 2) + 2 * (slot % 4) + slot / 4; }
+}
 
 #ifdef __cplusplus
 extern "C" {
@@ -143,8 +178,8 @@ int kvmix_quantize_pack(const kvmix_shape* shape, const kvmix_layer_cfg* cfg,
 /* Decode-time append of one token per sequence (Sec. 3.3, Fig. 4; Sec. 3.4 item 1):
  * k_new, v_new are fp16 [B][Hkv][128]. The token goes into the next window slot; when the
  * window then holds window + 32 tokens, the oldest 32 are quantized exactly as in
- * kvmix_quantize_pack and written at token offset n_q of the packed cache ("concatenation"
- * is an offset write into the pre-allocated cache). Updates n_q, n_w, w0 in *cache (host).
+ * kvmix_quantize_pack and written at token offset n_q of the packed cache (joining the new codes to the
+ * historical cache is an offset write into the pre-allocated buffer). Updates n_q, n_w, w0 in *cache (host).
  * With k_bits == 16 nothing is ever flushed (W_cap must hold the whole sequence). */
 int kvmix_append(const kvmix_shape* shape, const kvmix_layer_cfg* cfg,
                  const uint16_t* k_new, const uint16_t* v_new,
@@ -161,7 +196,7 @@ int kvmix_decode_attn(const kvmix_shape* shape, const kvmix_layer_cfg* cfg, cons
                       const kvmix_layer_cache* cache, float softmax_scale, uint16_t* out,
                       void* workspace, size_t workspace_bytes, int n_splits, void* stream);
 
-/* The same for n_tokens consecutive new tokens per sequence (chunked prefill, speculative decoding): exactly
+/* kvmix_append for n_tokens consecutive new tokens per sequence (chunked prefill, speculative decoding): exactly
  * n_tokens calls of kvmix_append in a row, with as many flushes of 32 tokens as fall due. Element (b, j, i, d)
  * of k_new / v_new is at b*batch_stride + j*head_stride + i*token_stride + d (strides in elements,
  * token_stride >= 128). Capacity (T_cap, W_cap) is checked for the whole call before anything is launched. */

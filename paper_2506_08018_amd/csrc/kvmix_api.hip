@@ -9,7 +9,21 @@ using namespace kvmix;
 namespace {
 
 std::atomic<int> g_last_hip_error{0};
-constexpr int kNumCUs = 256;   // MI355X
+
+constexpr int kMaxDevices = 64;
+
+// Compute units of the current device, asked once per device (0 when the query fails).
+int num_cus() {
+  static std::atomic<int> cached[kMaxDevices];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 0;
+  int n = cached[dev].load(std::memory_order_relaxed);
+  if (n == 0) {
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) return 0;
+    cached[dev].store(n, std::memory_order_relaxed);
+  }
+  return n;
+}
 
 int hip_fail(hipError_t e) {
   g_last_hip_error.store((int)e);
@@ -203,24 +217,34 @@ int kvmix_append(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const uint16
 
 namespace {
 
-// Validates and launches the attention kernel; with k_new / v_new the newest token of every unit is taken from
-// there (ring slot new_slot, not counted in n_w) and stored into the window by the kernel.
-int attention(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const uint16_t* q, const kvmix_layer_cache* c, int n_w,
-              const uint16_t* k_new, const uint16_t* v_new, int new_slot,
-              float softmax_scale, uint16_t* out, void* workspace, size_t workspace_bytes, int n_splits, void* stream) {
+// Everything an attention launch needs, filled by plan_attention after all host-side checks have passed.
+struct AttnPlan { AttnArgs a; int kb, vb, G, units; };
+
+size_t split_workspace_bytes(int units, int n_splits, int G) {
+  return counters_bytes(units) + (size_t)units * n_splits * G * (kD + 2) * sizeof(float);
+}
+
+// Validates an attention call against the cache state `c` (window count n_w) and fills the launch descriptor;
+// launches nothing. With k_new / v_new the newest token of every unit is taken from there (ring slot new_slot,
+// not counted in n_w) and stored into the window by the kernel.
+int plan_attention(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const uint16_t* q, const kvmix_layer_cache* c, int n_w,
+                   const uint16_t* k_new, const uint16_t* v_new, int new_slot,
+                   float softmax_scale, uint16_t* out, void* workspace, size_t workspace_bytes, int n_splits, AttnPlan* plan) {
   int st = check_shape_cfg(sh, cfg);
   if (st) return st;
   if (!q || !out) return KVMIX_ERR_NULL;
   if (!aligned16(q) || !aligned16(out)) return KVMIX_ERR_ALIGN;
   st = check_cache(cfg, c, false);
   if (st) return st;
-  if (c->n_q + n_w + (new_slot >= 0 ? 1 : 0) < 1 || n_w > c->W_cap) return KVMIX_ERR_BAD_SHAPE;
+  if (c->n_q + n_w + (new_slot >= 0 ? 1 : 0) < 1 || n_w < 0 || n_w > c->W_cap) return KVMIX_ERR_BAD_SHAPE;
   const int units = sh->B * sh->Hkv, G = sh->Hq / sh->Hkv;
   const int n_items = c->W_cap / kTile + c->n_q / kTile;
   if (n_splits < 0 || n_splits > max_splits(sh)) return KVMIX_ERR_BAD_SHAPE;
   if (n_splits == 0) {
-    // one workgroup occupies a whole CU (LDS): aim at one workgroup per CU, at least 8 tiles each
-    n_splits = kNumCUs / units;
+    // one workgroup occupies a whole compute unit (LDS): aim at one workgroup per unit, at least 8 tiles each
+    const int cus = num_cus();
+    if (cus == 0) return hip_fail(hipErrorInvalidDevice);
+    n_splits = cus / units;
     if (n_splits > n_items / 8) n_splits = n_items / 8;
     if (n_splits > max_splits(sh)) n_splits = max_splits(sh);
     if (n_splits < 1) n_splits = 1;
@@ -230,8 +254,7 @@ int attention(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const uint16_t*
   if (n_splits > 1) {
     if (!workspace) return KVMIX_ERR_NULL;
     if (!aligned16(workspace)) return KVMIX_ERR_ALIGN;
-    const size_t need = counters_bytes(units) + (size_t)units * n_splits * G * (kD + 2) * sizeof(float);
-    if (workspace_bytes < need) return KVMIX_ERR_WORKSPACE;
+    if (workspace_bytes < split_workspace_bytes(units, n_splits, G)) return KVMIX_ERR_WORKSPACE;
     a.counters = reinterpret_cast<uint32_t*>(workspace);
     a.part = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) + counters_bytes(units));
   }
@@ -243,8 +266,15 @@ int attention(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const uint16_t*
   a.Hq = sh->Hq; a.Hkv = sh->Hkv; a.n_splits = n_splits;
   const float scale = softmax_scale > 0.0f ? softmax_scale : 1.0f / std::sqrt((float)kD);
   a.scale_log2 = scale * 1.4426950408889634f;
-  const int kb = cfg->k_bits == 16 ? 2 : cfg->k_bits, vb = cfg->v_bits == 16 ? 2 : cfg->v_bits;
-  const hipError_t e = launch_decode_attn(a, kb, vb, G, units, (hipStream_t)stream);
+  plan->a = a;
+  plan->kb = cfg->k_bits == 16 ? 2 : cfg->k_bits;
+  plan->vb = cfg->v_bits == 16 ? 2 : cfg->v_bits;
+  plan->G = G; plan->units = units;
+  return KVMIX_OK;
+}
+
+int launch_plan(const AttnPlan& p, void* stream) {
+  const hipError_t e = launch_decode_attn(p.a, p.kb, p.vb, p.G, p.units, (hipStream_t)stream);
   return e == hipSuccess ? KVMIX_OK : hip_fail(e);
 }
 
@@ -254,12 +284,14 @@ extern "C" {
 
 int kvmix_decode_attn(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const uint16_t* q, const kvmix_layer_cache* c,
                       float softmax_scale, uint16_t* out, void* workspace, size_t workspace_bytes, int n_splits, void* stream) {
-  const int st = check_shape_cfg(sh, cfg);   // before the cache struct is looked at
-  if (st) return st;
+  const int st0 = check_shape_cfg(sh, cfg);   // before the cache struct is looked at
+  if (st0) return st0;
   if (!q || !out) return KVMIX_ERR_NULL;
   if (!aligned16(q) || !aligned16(out)) return KVMIX_ERR_ALIGN;
   if (!c) return KVMIX_ERR_NULL;
-  return attention(sh, cfg, q, c, c->n_w, nullptr, nullptr, -1, softmax_scale, out, workspace, workspace_bytes, n_splits, stream);
+  AttnPlan plan;
+  const int st = plan_attention(sh, cfg, q, c, c->n_w, nullptr, nullptr, -1, softmax_scale, out, workspace, workspace_bytes, n_splits, &plan);
+  return st ? st : launch_plan(plan, stream);
 }
 
 int kvmix_decode_step(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const uint16_t* k_new, const uint16_t* v_new,
@@ -268,12 +300,23 @@ int kvmix_decode_step(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const u
   int st = check_shape_cfg(sh, cfg);
   if (st) return st;
   if (!k_new || !v_new || !c) return KVMIX_ERR_NULL;
+  AttnPlan plan;
   const bool flush = cfg->k_bits != 16 && c->n_w + 1 == cfg->window + kTile;
   if (flush) {
-    // the 32 oldest window tokens move to the packed part before the attention reads them: two kernels, then attention
+    // The 32 oldest window tokens move to the packed part before the attention reads them: append, quantize-pack,
+    // then attention. Every check of all three is made first, the attention's against the counters as the append
+    // will leave them, so that a failing call launches nothing and leaves the counters alone.
+    st = check_cache(cfg, c, true);
+    if (st) return st;
+    if (c->n_q + kTile > c->T_cap || c->W_cap < cfg->window + kTile) return KVMIX_ERR_BAD_SHAPE;
+    if (!aligned16(k_new) || !aligned16(v_new)) return KVMIX_ERR_ALIGN;
+    kvmix_layer_cache after = *c;
+    after.n_q += kTile; after.n_w = c->n_w + 1 - kTile; after.w0 = (c->w0 + kTile) % c->W_cap;
+    st = plan_attention(sh, cfg, q, &after, after.n_w, nullptr, nullptr, -1, softmax_scale, out, workspace, workspace_bytes, n_splits, &plan);
+    if (st) return st;
     st = kvmix_append(sh, cfg, k_new, v_new, c, stream);
     if (st) return st;
-    return attention(sh, cfg, q, c, c->n_w, nullptr, nullptr, -1, softmax_scale, out, workspace, workspace_bytes, n_splits, stream);
+    return launch_plan(plan, stream);
   }
   st = check_cache(cfg, c, cfg->k_bits != 16);
   if (st) return st;
@@ -282,7 +325,9 @@ int kvmix_decode_step(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const u
   if (!aligned16(k_new) || !aligned16(v_new)) return KVMIX_ERR_ALIGN;
   const int slot = (c->w0 + c->n_w) % c->W_cap;
   // the kernel's window count excludes the new token: it is added as a term of its own (and stored)
-  st = attention(sh, cfg, q, c, c->n_w, k_new, v_new, slot, softmax_scale, out, workspace, workspace_bytes, n_splits, stream);
+  st = plan_attention(sh, cfg, q, c, c->n_w, k_new, v_new, slot, softmax_scale, out, workspace, workspace_bytes, n_splits, &plan);
+  if (st) return st;
+  st = launch_plan(plan, stream);
   if (st) return st;
   c->n_w += 1;
   return KVMIX_OK;

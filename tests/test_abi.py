@@ -20,6 +20,8 @@ def kv():
 def declared_functions():
     text = open(HEADER).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    text = re.sub(r"static inline[^{]*\{.*?\n\}", "", text, flags=re.S)      # header-only helpers are not exports
+    text = re.sub(r"static inline[^{]*\{[^\n]*\}", "", text)
     return sorted(set(re.findall(r"\b(kvmix_[a-z_0-9]+)\s*\(", text)))
 
 
@@ -105,6 +107,32 @@ def test_decode_step_checks_its_cache_on_the_host(kv):
     ok = _CacheStruct(4096, 4096, 4096, 64, 64, 0, 5, 0)
     assert L.kvmix_decode_step(C.byref(sh), C.byref(cfg), odd, a, a, C.byref(ok), C.c_float(0.0), a, None, 0, 0, None) == -5
     assert ok.n_w == 5
+
+
+def test_decode_step_on_the_flush_step_checks_the_attention_first(kv):
+    """The step on which the window overflows (append, quantize-pack, attention) validates the attention's own
+    arguments before the append is launched: a failing call has moved no counter."""
+    import ctypes as C
+    from paper_2506_08018_amd.binding import _CacheStruct
+    L = kv.lib()
+    sh, cfg = kv.Shape(1, 4, 4), kv.LayerCfg(2, 2, 32)
+    a = C.c_void_p(4096)
+
+    def due():
+        return _CacheStruct(4096, 4096, 4096, 128, 64, 32, 63, 32)      # n_w == window + 31: this append overflows
+
+    c = due()
+    assert L.kvmix_decode_step(C.byref(sh), C.byref(cfg), a, a, None, C.byref(c), C.c_float(0.0), a, None, 0, 1, None) == -1      # q
+    assert (c.n_q, c.n_w, c.w0) == (32, 63, 32)
+    assert L.kvmix_decode_step(C.byref(sh), C.byref(cfg), a, a, a, C.byref(c), C.c_float(0.0), None, None, 0, 1, None) == -1      # out
+    assert L.kvmix_decode_step(C.byref(sh), C.byref(cfg), a, a, C.c_void_p(4104), C.byref(c), C.c_float(0.0), a, None, 0, 1, None) == -5
+    assert L.kvmix_decode_step(C.byref(sh), C.byref(cfg), a, a, a, C.byref(c), C.c_float(0.0), a, a, 64, 2, None) == -6           # workspace of 64 bytes
+    assert L.kvmix_decode_step(C.byref(sh), C.byref(cfg), a, a, a, C.byref(c), C.c_float(0.0), a, None, 0, 2, None) == -1         # splits without workspace
+    assert L.kvmix_decode_step(C.byref(sh), C.byref(cfg), a, a, a, C.byref(c), C.c_float(0.0), a, a, 1 << 20, 99, None) == -4     # split count
+    assert (c.n_q, c.n_w, c.w0) == (32, 63, 32)
+    full = _CacheStruct(4096, 4096, 4096, 32, 64, 32, 63, 32)            # no room for another packed tile
+    assert L.kvmix_decode_step(C.byref(sh), C.byref(cfg), a, a, a, C.byref(full), C.c_float(0.0), a, None, 0, 1, None) == -4
+    assert (full.n_q, full.n_w, full.w0) == (32, 63, 32)
 
 
 def test_append_tokens_checks_capacity_for_the_whole_call(kv):
