@@ -221,6 +221,13 @@ int kvmix_decode_step(const kvmix_shape* shape, const kvmix_layer_cfg* cfg,
 int kvmix_dequant(const kvmix_shape* shape, const kvmix_layer_cfg* cfg,
                   const kvmix_layer_cache* cache, int which, float* out, void* stream);
 
+/* Benchmark helper: a load-only pass over `bytes` bytes of device memory at `buf` (16-byte aligned) in the
+ * attention kernel's launch shape: `workgroups` workgroups of `threads` threads (multiple of 64, <= 768), each
+ * reading one contiguous span with 16-byte loads under the same cache policy. Nothing is computed or written
+ * (`sink`, 4 bytes of device memory or NULL, is only there to keep the loads alive). Timed next to the attention
+ * launch it gives the read rate a launch of that shape and size can reach on the machine at hand. */
+int kvmix_stream_read(const void* buf, size_t bytes, int workgroups, int threads, void* sink, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -4,7 +4,7 @@ Every step of the path runs in the HIP kernels of csrc/; this package only marsh
 PyTorch is used for device memory and streams.
 """
 from .binding import (KVMixError, LayerCache, LayerCfg, Shape, append, append_tokens, cache_bytes, decode_attn, decode_step, dequant, lib,
-                      quantize_pack, strerror, version, workspace_bytes)
+                      quantize_pack, stream_read, strerror, version, workspace_bytes)
 
 __all__ = ["KVMixError", "LayerCache", "LayerCfg", "Shape", "append", "append_tokens", "cache_bytes", "decode_attn", "decode_step", "dequant", "lib",
-           "quantize_pack", "strerror", "version", "workspace_bytes"]
+           "quantize_pack", "stream_read", "strerror", "version", "workspace_bytes"]

@@ -60,6 +60,8 @@ def lib():
         L.kvmix_decode_attn.argtypes = [P, P, P, P, C.c_float, P, P, SZ, I, P]
         L.kvmix_decode_step.restype = I
         L.kvmix_decode_step.argtypes = [P, P, P, P, P, P, C.c_float, P, P, SZ, I, P]
+        L.kvmix_stream_read.restype = I
+        L.kvmix_stream_read.argtypes = [P, SZ, I, I, P, P]
         L.kvmix_dequant.restype = I
         L.kvmix_dequant.argtypes = [P, P, P, I, P, P]
         _lib = L
@@ -182,6 +184,13 @@ def decode_step(shape, cfg, k_new, v_new, q, cache, out, workspace=None, softmax
                                  C.byref(cache.c), C.c_float(softmax_scale), out.data_ptr(), wp, wn, n_splits, _stream(stream))
     _check(st, "kvmix_decode_step")
     return out
+
+
+def stream_read(buf, workgroups, threads=768, nbytes=None, sink=None, stream=None):
+    """Load-only pass over the first nbytes (default: all) of the CUDA tensor `buf` in the attention kernel's launch shape."""
+    n = buf.numel() * buf.element_size() if nbytes is None else int(nbytes)
+    st = lib().kvmix_stream_read(buf.data_ptr(), n, workgroups, threads, sink.data_ptr() if sink is not None else None, _stream(stream))
+    _check(st, "kvmix_stream_read")
 
 
 def dequant(shape, cfg, cache, which, out):

@@ -333,6 +333,14 @@ int kvmix_decode_step(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const u
   return KVMIX_OK;
 }
 
+int kvmix_stream_read(const void* buf, size_t bytes, int workgroups, int threads, void* sink, void* stream) {
+  if (!buf) return KVMIX_ERR_NULL;
+  if (!aligned16(buf)) return KVMIX_ERR_ALIGN;
+  if (workgroups < 1 || workgroups > 65535 || threads < 64 || threads > 768 || threads % 64) return KVMIX_ERR_BAD_SHAPE;
+  const hipError_t e = launch_stream_read(buf, bytes, workgroups, threads, reinterpret_cast<uint32_t*>(sink), (hipStream_t)stream);
+  return e == hipSuccess ? KVMIX_OK : hip_fail(e);
+}
+
 int kvmix_dequant(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const kvmix_layer_cache* c, int which, float* out, void* stream) {
   int st = check_shape_cfg(sh, cfg);
   if (st) return st;

@@ -106,6 +106,7 @@ hipError_t launch_quantize_pack(const QuantArgs& a, int k_bits, int v_bits,
                                 int n_tiles, int units, hipStream_t s);
 hipError_t launch_dequant(const DequantArgs& a, int units, hipStream_t s);
 hipError_t launch_append(const AppendArgs& a, hipStream_t s);
+hipError_t launch_stream_read(const void* buf, size_t bytes, int workgroups, int threads, uint32_t* sink, hipStream_t s);
 hipError_t launch_decode_attn(const AttnArgs& a, int k_bits, int v_bits, int G, int units, hipStream_t s);
 
 }  // namespace kvmix

@@ -310,6 +310,26 @@ __global__ __launch_bounds__(128) void append_kernel(AppendArgs a) {
   a.v_win[dst] = a.v_new[src];
 }
 
+// Load-only pass over a buffer in the launch shape of the attention kernel (one workgroup per contiguous span,
+// 16 bytes per lane and load, non-temporal policy, four loads in flight per lane): the rate a kernel of this
+// shape can reach on the machine at hand when it does nothing but read.
+__global__ __launch_bounds__(768) void stream_read_kernel(const u32x4_t* buf, size_t n16, uint32_t* sink) {
+  const size_t per_wg = (n16 + gridDim.x - 1) / gridDim.x;
+  const size_t begin = (size_t)blockIdx.x * per_wg;
+  const size_t end = begin + per_wg < n16 ? begin + per_wg : n16;
+  const size_t step = blockDim.x;
+  u32x4_t acc = {0, 0, 0, 0};
+  size_t i = begin + threadIdx.x;
+  for (; i + 3 * step < end; i += 4 * step) {
+    const u32x4_t a = __builtin_nontemporal_load(buf + i), b = __builtin_nontemporal_load(buf + i + step);
+    const u32x4_t c = __builtin_nontemporal_load(buf + i + 2 * step), d = __builtin_nontemporal_load(buf + i + 3 * step);
+    acc |= (a ^ b) | (c ^ d);
+  }
+  for (; i < end; i += step) acc |= __builtin_nontemporal_load(buf + i);
+  // never true for real data in all four words at once: keeps the loads alive without a store per lane
+  if ((acc[0] & acc[1] & acc[2] & acc[3]) == 0xFFFFFFFFu && sink) sink[0] = 1u;
+}
+
 template <int KB, int VB>
 hipError_t launch_qp(const QuantArgs& a, dim3 grid, hipStream_t s) {
   quantize_pack_kernel<KB, VB><<<grid, 128, 0, s>>>(a);
@@ -346,6 +366,12 @@ hipError_t launch_quantize_pack(const QuantArgs& a, int k_bits, int v_bits,
 hipError_t launch_dequant(const DequantArgs& a, int units, hipStream_t s) {
   if (a.n_tiles == 0 || units == 0) return hipSuccess;
   dequant_kernel<<<dim3(a.n_tiles, units), 256, 0, s>>>(a);
+  return hipGetLastError();
+}
+
+hipError_t launch_stream_read(const void* buf, size_t bytes, int workgroups, int threads, uint32_t* sink, hipStream_t s) {
+  if (bytes < 16 || workgroups < 1) return hipSuccess;
+  stream_read_kernel<<<workgroups, threads, 0, s>>>(reinterpret_cast<const u32x4_t*>(buf), bytes / 16, sink);
   return hipGetLastError();
 }
 

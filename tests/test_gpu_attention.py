@@ -7,7 +7,7 @@ from gpu_common import assert_attn_close, assert_cache_equal, bits_of, make_pair
 
 pytestmark = pytest.mark.gpu
 
-COMBOS = [(kb, vb) for kb in (2, 3, 4) for vb in (2, 3, 4)] + [(1, 1), (1, 2), (2, 1), (1, 4), (3, 1)]
+COMBOS = [(kb, vb) for kb in (1, 2, 3, 4) for vb in (1, 2, 3, 4)]      # every pair the launch tables instantiate
 
 
 @pytest.mark.parametrize("kb,vb", COMBOS)
@@ -20,6 +20,17 @@ def test_all_bit_combos(kb, vb, G):
     assert st == 0
     got = run_attn(gc, shape, cfg, q)
     assert_attn_close(got, want, f"kb={kb} vb={vb} G={G}", tight=True)
+
+
+@pytest.mark.parametrize("kb,vb", [(1, 1), (1, 3), (4, 1), (2, 1)])
+@pytest.mark.parametrize("G,n_splits", [(8, 1), (8, 3), (2, 3), (4, 1)])
+def test_one_bit_settings_across_groups_and_splits(kb, vb, G, n_splits):
+    print(f"case one-bit kb={kb} vb={vb} G={G} splits={n_splits}", flush=True)
+    q, k, v, rc, gc, shape, cfg = make_pair(1, 2 * G, 2, 32 * 26 + 11, 32, kb, vb, seed=250 + kb * 10 + vb + G)
+    st, want = rc.decode_attn(u16(q))
+    assert st == 0
+    got = run_attn(gc, shape, cfg, q, n_splits=n_splits)
+    assert_attn_close(got, want, f"kb={kb} vb={vb} G={G} splits={n_splits}", tight=True)
 
 
 @pytest.mark.parametrize("G", [1, 2, 4, 8])
@@ -101,6 +112,28 @@ def test_sharp_softmax_and_large_values():
     # outputs above 2 have an fp16 spacing wider than the absolute bound: allow one spacing there
     bad = np.argwhere(err > np.maximum(2e-3, 1.01 * ulp))
     assert len(bad) == 0, [(tuple(i), h2f64(want)[tuple(i)], h2f64(got)[tuple(i)]) for i in bad[:5]]
+
+
+@pytest.mark.parametrize("G,kb,vb", [(1, 2, 2), (4, 3, 4), (8, 2, 3)])
+def test_stale_ring_slots_and_key_outliers(G, kb, vb):
+    """(a) Ring slots outside the live window hold large finite leftovers (not zeros): they are masked, the result
+    does not change. (b) Key channel outliers of x100 (group scales in the hundreds, folded into fp16 operands)."""
+    import torch
+    print(f"case stale slots / outliers G={G} kb={kb} vb={vb}", flush=True)
+    B, Hkv, T, W = 1, 2, 32 * 14 + 9, 32
+    q, k, v = synth.gen_layer_numpy(720 + G, 0, B, Hkv * G, Hkv, T)
+    k[:, :, :, 5] *= 10.0          # on top of the generator's x10 channels: up to x100
+    k[:, 1, :, 77] *= 100.0
+    _, _, _, rc, gc, shape, cfg = make_pair(B, Hkv * G, Hkv, T, W, kb, vb, W_cap=128, q_k_v=(q, k, v))
+    assert gc.n_w == 41 and gc.W_cap == 128
+    junk_k = torch.full((shape.units, 128 - 41, 128), 6.0e4, dtype=torch.float16, device="cuda")
+    junk_v = torch.full((shape.units, 128 - 41, 128), -6.0e4, dtype=torch.float16, device="cuda")
+    gc.k_win.view(torch.float16).view(shape.units, 128, 128)[:, 41:] = junk_k
+    gc.v_win.view(torch.float16).view(shape.units, 128, 128)[:, 41:] = junk_v
+    st, want = rc.decode_attn(u16(q))
+    assert st == 0
+    for ns in (1, 2):
+        assert_attn_close(run_attn(gc, shape, cfg, q, n_splits=ns), want, f"stale slots G={G} splits={ns}")
 
 
 @pytest.mark.parametrize("kb,vb,G", [(2, 2, 1), (3, 4, 4)])

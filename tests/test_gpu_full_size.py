@@ -56,20 +56,22 @@ def test_full_size_sampled_units(name, n_sample):
         del q, k, v, gc, out
 
 
-def test_full_size_fused_step_cfg2():
-    """kvmix_decode_step at the benchmark's shape and launch configuration (256 units, one workgroup each):
-    the appended token, the flush that follows 8 steps later and the attention over both, on sampled units."""
+@pytest.mark.parametrize("name,kb,vb,layer,steps", [("cfg2_llama2_7b", 3, 2, 5, 10), ("cfg3_mistral_7b_gqa", 2, 4, 6, 12),
+                                                    ("cfg5_70b_stress", 3, 4, 7, 16)])
+def test_full_size_fused_steps(name, kb, vb, layer, steps):
+    """kvmix_decode_step at a benchmark shape and in its launch configuration (library-chosen split count; query
+    groups of 1, 4 and 8 heads): the appended tokens, the flush that falls due 8 steps into the run and the attention
+    over both, at every step, on sampled units."""
     import torch
     import paper_2506_08018_amd as kv
     from oracle.kvmix_ref import RefCache
-    c = synth.CONFIGS["cfg2_llama2_7b"]
+    c = synth.CONFIGS[name]
     B, Hq, Hkv, T, W = c["B"], c["Hq"], c["Hkv"], c["T"], c["W"]
+    G = Hq // Hkv
     n_w0 = W + 24
     n_q0 = T - 8 - n_w0
-    steps = 10
-    kb, vb = 3, 2
     shape, cfg = kv.Shape(B, Hq, Hkv), kv.LayerCfg(kb, vb, W)
-    q, k, v = synth.gen_layer_torch("cuda", synth.BASE_SEED, 5, B, Hq, Hkv, n_q0 + n_w0 + steps)
+    q, k, v = synth.gen_layer_torch("cuda", synth.BASE_SEED, layer, B, Hq, Hkv, n_q0 + n_w0 + steps)
     gc = kv.LayerCache(shape, cfg, T + 64, W + 32)
     kv.quantize_pack(shape, cfg, k[:, :, :n_q0], v[:, :, :n_q0], gc)
     gc.set_window(k[:, :, n_q0:n_q0 + n_w0], v[:, :, n_q0:n_q0 + n_w0])
@@ -79,20 +81,29 @@ def test_full_size_fused_step_cfg2():
     for u in units:
         b, j = divmod(int(u), Hkv)
         ku, vu = t16(k[b, j]).reshape(1, 1, -1, 128), t16(v[b, j]).reshape(1, 1, -1, 128)
-        rc = RefCache(1, 1, 1, kb, vb, W, T + 64, W + 32)
+        rc = RefCache(1, G, 1, kb, vb, W, T + 64, W + 32)
         assert rc.quantize_pack(ku[:, :, :n_q0], vu[:, :, :n_q0]) == 0
         rc.set_window(ku[:, :, n_q0:n_q0 + n_w0], vu[:, :, n_q0:n_q0 + n_w0])
         refs.append((b, j, ku, vu, rc))
     out = torch.zeros_like(q)
+    rng = np.random.default_rng(13)
     for s in range(steps):
-        print(f"case cfg2 fused step {s}", flush=True)
+        print(f"case {name} fused step {s}", flush=True)
         t = n_q0 + n_w0 + s
-        kv.decode_step(shape, cfg, k[:, :, t].contiguous(), v[:, :, t].contiguous(), q, gc, out, ws)
+        qs = (q.float() * float(rng.uniform(0.6, 1.4))).half()                       # a fresh query every step
+        kv.decode_step(shape, cfg, k[:, :, t].contiguous(), v[:, :, t].contiguous(), qs, gc, out, ws)
         torch.cuda.synchronize()
         for b, j, ku, vu, rc in refs:
             assert rc.append(ku[:, :, t], vu[:, :, t]) == 0
             assert (gc.n_q, gc.n_w, gc.w0) == (rc.n_q, rc.n_w, rc.w0)
-            st, want = rc.decode_attn(t16(q[b, j:j + 1]).reshape(1, 1, 128))
+            st, want = rc.decode_attn(t16(qs[b, j * G:(j + 1) * G]).reshape(1, G, 128))
             assert st == 0
-            assert_attn_close(t16(out[b, j:j + 1]).reshape(1, 1, 128), want, f"cfg2 fused step {s} unit {(b, j)}", tight=True)
+            assert_attn_close(t16(out[b, j * G:(j + 1) * G]).reshape(1, G, 128), want, f"{name} fused step {s} unit {(b, j)}", tight=True,
+                              tight_abs=2.5e-4)
     assert gc.n_q == n_q0 + 32     # the flush happened inside the run
+    assert not ws[: 4 * shape.units].any()
+    tiles = (T + 64) // 32
+    records = gc.packed.view(torch.int32).view(B * Hkv, tiles, -1)
+    for (b, j, ku, vu, rc), u in zip(refs, units):                                   # the flushed tile, bit for bit
+        nt = rc.n_q // 32
+        assert np.array_equal(records[int(u), :nt].cpu().numpy().view(np.uint32), rc.packed[0, :nt]), f"tile records of unit {u}"
