@@ -196,6 +196,20 @@ int kvmix_decode_attn(const kvmix_shape* shape, const kvmix_layer_cfg* cfg, cons
                       const kvmix_layer_cache* cache, float softmax_scale, uint16_t* out,
                       void* workspace, size_t workspace_bytes, int n_splits, void* stream);
 
+/* kvmix_decode_attn for callers that cannot allocate or hand over a workspace (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): same arguments and result, but the split partials and
+ * arrival counters live in a fixed array of KVMIX_STATIC_SCRATCH_BYTES that is part of the library's device
+ * image (each GPU the library runs on holds its own copy until the process ends). The call allocates nothing.
+ * It returns KVMIX_ERR_WORKSPACE when the (explicit or library-chosen) split count needs more than the array
+ * holds: units * n_splits * G * 520 bytes + 4 bytes per unit rounded up to 256. The first call on a device looks
+ * up the array's address and clears its counters on `stream`; make that call with the device current and outside
+ * any graph capture. All calls on one GPU share the array: calls that overlap in time on one GPU (different
+ * streams) race; calls on one stream, or otherwise ordered, are safe. */
+#define KVMIX_STATIC_SCRATCH_BYTES ((size_t)4 << 20)
+int kvmix_decode_attn_static(const kvmix_shape* shape, const kvmix_layer_cfg* cfg, const uint16_t* q,
+                             const kvmix_layer_cache* cache, float softmax_scale, uint16_t* out,
+                             int n_splits, void* stream);
+
 /* kvmix_append for n_tokens consecutive new tokens per sequence (chunked prefill, speculative decoding): exactly
  * n_tokens calls of kvmix_append in a row, with as many flushes of 32 tokens as fall due. Element (b, j, i, d)
  * of k_new / v_new is at b*batch_stride + j*head_stride + i*token_stride + d (strides in elements,

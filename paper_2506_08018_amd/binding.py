@@ -58,6 +58,8 @@ def lib():
         L.kvmix_append_tokens.argtypes = [P, P, P, P, I64, I64, I64, I, P, P]
         L.kvmix_decode_attn.restype = I
         L.kvmix_decode_attn.argtypes = [P, P, P, P, C.c_float, P, P, SZ, I, P]
+        L.kvmix_decode_attn_static.restype = I
+        L.kvmix_decode_attn_static.argtypes = [P, P, P, P, C.c_float, P, I, P]
         L.kvmix_decode_step.restype = I
         L.kvmix_decode_step.argtypes = [P, P, P, P, P, P, C.c_float, P, P, SZ, I, P]
         L.kvmix_stream_read.restype = I
@@ -173,6 +175,15 @@ def decode_attn(shape, cfg, q, cache, out, workspace=None, softmax_scale=0.0, n_
     st = lib().kvmix_decode_attn(C.byref(shape), C.byref(cfg), q.data_ptr(), C.byref(cache.c), C.c_float(softmax_scale),
                                  out.data_ptr(), wp, wn, n_splits, _stream(stream))
     _check(st, "kvmix_decode_attn")
+    return out
+
+
+def decode_attn_static(shape, cfg, q, cache, out, softmax_scale=0.0, n_splits=0, stream=None):
+    """decode_attn without a workspace argument: the split partials live in the library's own fixed device array."""
+    assert q.is_contiguous() and out.is_contiguous()
+    st = lib().kvmix_decode_attn_static(C.byref(shape), C.byref(cfg), q.data_ptr(), C.byref(cache.c), C.c_float(softmax_scale),
+                                        out.data_ptr(), n_splits, _stream(stream))
+    _check(st, "kvmix_decode_attn_static")
     return out
 
 

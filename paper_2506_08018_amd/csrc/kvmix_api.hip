@@ -2,6 +2,7 @@
 // Contract and layout: include/kvmix.h.
 #include <atomic>
 #include <cmath>
+#include <mutex>
 #include "kvmix_common.hpp"
 
 using namespace kvmix;
@@ -278,6 +279,43 @@ int launch_plan(const AttnPlan& p, void* stream) {
   return e == hipSuccess ? KVMIX_OK : hip_fail(e);
 }
 
+// ---- split workspace of kvmix_decode_attn_static: a fixed array in device memory, one copy per GPU
+constexpr size_t kScratchBytes = KVMIX_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+// In host code the array's name is only a handle; its address on a device comes from hipGetSymbolAddress,
+// asked once per device with that device current. Each GPU holds its own copy at its own address.
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+__global__ void clear_words_kernel(uint32_t* p, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0u;
+}
+
+// Address of the current device's copy of `scratch`. The first call on a device also clears the arrival
+// counters at the array's start (on `stream`, ahead of the first launch that uses them); afterwards every
+// attention launch leaves them zero again.
+int scratch_address(void** ptr, hipStream_t stream) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e);
+  if (dev < 0 || dev >= kMaxDevices) return hip_fail(hipErrorInvalidDevice);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return hip_fail(e);
+    if (!p) return hip_fail(hipErrorInvalidSymbol);
+    constexpr int kCounterWords = 65536;       // units <= 65535
+    clear_words_kernel<<<kCounterWords / 256, 256, 0, stream>>>(reinterpret_cast<uint32_t*>(p), kCounterWords);
+    e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e);
+    g_scratch_ptr[dev] = p;
+  }
+  *ptr = g_scratch_ptr[dev];
+  return KVMIX_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -292,6 +330,31 @@ int kvmix_decode_attn(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const u
   AttnPlan plan;
   const int st = plan_attention(sh, cfg, q, c, c->n_w, nullptr, nullptr, -1, softmax_scale, out, workspace, workspace_bytes, n_splits, &plan);
   return st ? st : launch_plan(plan, stream);
+}
+
+int kvmix_decode_attn_static(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const uint16_t* q, const kvmix_layer_cache* c,
+                             float softmax_scale, uint16_t* out, int n_splits, void* stream) {
+  const int st0 = check_shape_cfg(sh, cfg);
+  if (st0) return st0;
+  if (!q || !out) return KVMIX_ERR_NULL;
+  if (!aligned16(q) || !aligned16(out)) return KVMIX_ERR_ALIGN;
+  if (!c) return KVMIX_ERR_NULL;
+  AttnPlan plan;
+  // First pass with a workspace of "any size" at a dummy aligned address: settles the split count and runs
+  // every other check; the size that split count needs is then held against the array's fixed size.
+  int st = plan_attention(sh, cfg, q, c, c->n_w, nullptr, nullptr, -1, softmax_scale, out, reinterpret_cast<void*>(256), ~(size_t)0, n_splits, &plan);
+  if (st) return st;
+  if (plan.a.n_splits > 1) {
+    if (split_workspace_bytes(plan.units, plan.a.n_splits, plan.G) > kScratchBytes) return KVMIX_ERR_WORKSPACE;
+    void* ptr = nullptr;
+    st = scratch_address(&ptr, (hipStream_t)stream);
+    if (st) return st;
+    plan.a.counters = reinterpret_cast<uint32_t*>(ptr);
+    plan.a.part = reinterpret_cast<float*>(reinterpret_cast<char*>(ptr) + counters_bytes(plan.units));
+  } else {
+    plan.a.counters = nullptr; plan.a.part = nullptr;
+  }
+  return launch_plan(plan, stream);
 }
 
 int kvmix_decode_step(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const uint16_t* k_new, const uint16_t* v_new,

@@ -135,6 +135,17 @@ def test_decode_step_on_the_flush_step_checks_the_attention_first(kv):
     assert (full.n_q, full.n_w, full.w0) == (32, 63, 32)
 
 
+def test_static_scratch_entry_point_validates_like_the_workspace_one(kv):
+    import ctypes as C
+    L = kv.lib()
+    sh, cfg = kv.Shape(1, 4, 4), kv.LayerCfg(2, 2, 32)
+    a = C.c_void_p(4096)
+    assert L.kvmix_decode_attn_static(C.byref(sh), C.byref(cfg), None, a, C.c_float(0.0), a, 1, None) == -1
+    assert L.kvmix_decode_attn_static(C.byref(sh), C.byref(cfg), a, None, C.c_float(0.0), a, 1, None) == -1
+    assert L.kvmix_decode_attn_static(C.byref(sh), C.byref(cfg), C.c_void_p(4104), a, C.c_float(0.0), a, 1, None) == -5
+    assert L.kvmix_decode_attn_static(C.byref(kv.Shape(1, 12, 4)), C.byref(cfg), a, a, C.c_float(0.0), a, 1, None) == -4
+
+
 def test_append_tokens_checks_capacity_for_the_whole_call(kv):
     """A multi-token append that would overflow the packed capacity or the ring is refused as a whole:
     nothing is launched, the counters stay as they were."""
