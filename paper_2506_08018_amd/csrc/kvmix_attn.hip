@@ -31,10 +31,17 @@ namespace kvmix {
 namespace {
 
 // waves per workgroup: 3 per SIMD where the LDS exchange areas fit (register budget 512 / 3 per lane)
-constexpr int waves_for(int G) { return G == 8 ? 8 : 12; }
+constexpr int waves_for(int G) { return 12; }
 constexpr int kDepth = 1;            // tiles a wave requests ahead; 2 and 3 measured no faster (the loop runs at the memory system's rate)
-constexpr int kMergeBatch = 8;           // splits whose partials the merging workgroup requests together (one round trip)
-constexpr float kRefMargin = 4.0f;   // reference maximum is raised to (tile max + margin), log2 units
+constexpr int kMergeBatch = 32;          // splits whose partials the merging workgroup requests together (one round trip)
+// Reference of the running softmax (log2 units): numerators 2^(score - reference) are kept at or below 2^kRefCap;
+// when a score would exceed that, the reference is raised to (that score - kRefCap + 4), which leaves room for
+// scores 16 times larger before the next raise. Numerators are large on purpose: they and their products with
+// the Value scales travel as fp16 pairs whose absolute resolution is 2^-25, and the thousands of low-weight
+// tokens of a long context sit near that floor; with numerators up to 2^6 instead of 1 the floor is 64 times
+// lower relative to the sums. The price is the range: a Value group scale must stay below 2^16 / 2^6 = 1024.
+constexpr float kRefCap = 6.0f;
+constexpr float kRefMargin = 4.0f - kRefCap;
 
 typedef float float2_t __attribute__((ext_vector_type(2)));
 
@@ -220,7 +227,19 @@ template <int KB, int VB> struct Stage {
 __device__ __forceinline__ void st_agent(float* p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 __device__ __forceinline__ float ld_agent(const float* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 
-// fp32 pair -> packed fp16 pairs (hi, lo) with hi + lo == x to ~22 bits
+__device__ __forceinline__ half2_t as_half2(uint32_t v) { return __builtin_bit_cast(half2_t, v); }
+__device__ __forceinline__ uint32_t as_u32(half2_t v) { return __builtin_bit_cast(uint32_t, v); }
+// Product of two fp16 pairs as packed fp16 pairs (hi, lo) with hi + lo == a * b to ~21 bits: hi is the product
+// rounded to fp16 (one packed multiply), lo the residual of the exact product against that same register (one
+// packed fused multiply-add; the residual of an fp16 product is itself an fp16 number unless it falls below
+// 2^-24, where it is off by at most 2^-25 absolute).
+__device__ __forceinline__ void mul_split(half2_t a, half2_t b, uint32_t& hi, uint32_t& lo) {
+  const half2_t h = a * b;
+  const half2_t l = __builtin_elementwise_fma(a, b, -h);
+  hi = as_u32(h);
+  lo = as_u32(l);
+}
+// fp32 pair -> packed fp16 pairs (hi, lo) with hi + lo == x to ~22 bits.
 // The hi parts come from the truncating packed conversion, an intrinsic of its own: written as a plain
 // cast, the multiply that produced x may get fused into one of the two uses of the hi part only, and the
 // stored hi part and the one the lo part refers to then differ by a double rounding.
@@ -240,22 +259,22 @@ __device__ __forceinline__ half_t split_part(float x, bool lo_part) {
 __device__ __forceinline__ float lo_half(uint32_t v) { return (float)__builtin_bit_cast(half_t, (uint16_t)(v & 0xffffu)); }
 __device__ __forceinline__ float hi_half(uint32_t v) { return (float)__builtin_bit_cast(half_t, (uint16_t)(v >> 16)); }
 
-// Wave-private LDS exchange area. Operand rows exist for the 2*G used MFMA columns only (hi parts in
-// rows 0..G-1, lo parts in rows G..2G-1); the lanes of unused columns all read the extra zero row.
+// Wave-private LDS exchange area. Operand rows exist for the 2*G used MFMA columns only (row 2h holds the hi
+// parts of head h, row 2h+1 its lo parts: neighbours, so that one two-address LDS write stores both); the lanes
+// of unused columns all read an extra zero row.
 // Row pitches (272 B, 80 B) put the rows read by one 16-byte operand load into distinct banks.
 template <int G> struct __attribute__((aligned(16))) WaveLds {
-  static constexpr int kRows = 2 * G;      // index of the zero row
-  uint16_t bk[kRows + 1][kD + 8];          // scale-folded query [row][channel]
+  static constexpr int kRows = 2 * G;                 // index of the zero row (present when columns are unused)
+  static constexpr int kZeroRow = kRows < 16 ? 1 : 0;
+  uint16_t bk[kRows + kZeroRow][kD + 8];   // scale-folded query [row][channel]
   uint16_t zk[kD];                         // Key zero-points of the tile
-  float s[2 * G][kTile];                   // raw code sums of the tile [row][token] (hi rows, then lo rows)
-  uint16_t bv[4][kRows + 1][kTile + 8];    // scale-folded probabilities [channel block][row][token]
-  uint16_t pb[kRows + 1][kTile + 8];       // probabilities split hi/lo [row][token]
+  float s[2 * G][kTile];                   // scores of the tile in the log2 domain, reference subtracted [row][token] (rows as in bk)
+  uint16_t bv[4][kRows + kZeroRow][kTile + 8];   // scale-folded softmax numerators [channel block][row][token]
+  uint16_t pq[kRows + 1][kTile + 8];       // softmax numerators as two fp16 terms [row][token] (rows as in bk); the last row stays zero
   uint16_t zv[4][kTile];                   // Value zero-points [channel block][token]
-  float pp[G][kTile];                      // softmax numerators [head][token] (groups of 4 or 8 heads)
 };
 
-template <int G> struct __attribute__((aligned(16))) MergeLds {        // per-wave results (its own memory: a wave that is done never waits for the others)
-  float o[waves_for(G)][G][kD];
+template <int G> struct MergeLds {        // per-wave reference maximum and sum of numerators of every head
   float m[waves_for(G)][G];
   float l[waves_for(G)][G];
 };
@@ -267,7 +286,9 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
   // per wave: the exchange area of the packed tiles; before that, the staging area in which a window tile's
   // Value rows (token-major in memory) are turned into matrix-core operands (8 consecutive tokens per lane)
   constexpr int kTPitch = kD + 8;   // fp16 elements per staged row (272 B: 16-byte aligned rows)
-  union WaveArea { WaveLds<G> x; uint16_t t[kTile][kTPitch]; };
+  // and, once the wave has worked through its tiles, its result (a wave's memory is its own: a wave that is
+  // done never waits for the others)
+  union WaveArea { WaveLds<G> x; uint16_t t[kTile][kTPitch]; float o[G][kD]; };
   __shared__ WaveArea s_wave[kWaves];
   __shared__ MergeLds<G> R;
   __shared__ int s_next;   // next unclaimed packed tile of this workgroup
@@ -282,7 +303,7 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
   const int b = u / a.Hkv, jh = u % a.Hkv;
   WaveLds<G>& L = s_wave[wave].x;
   uint16_t (&T)[kTile][kTPitch] = s_wave[wave].t;
-  const int row = col_valid ? (lo_part ? G + h : h) : WaveLds<G>::kRows;   // operand row of this lane's column
+  const int row = col_valid ? 2 * h + (lo_part ? 1 : 0) : WaveLds<G>::kRows;   // operand row of this lane's column
 
   // work items of this split: window tiles first, then packed tiles
   const int n_wt = a.W_cap / kTile;
@@ -369,21 +390,27 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
   if (wi < win_end) win_load(wi, wt);
 
   if (tid == 0) { s_next = p_begin + kDepth * n_early; s_done = 0; }
-  __syncthreads();   // the only workgroup barrier before the results are merged: the counters are set
+  // The only workgroup barrier before the results are merged: the counters are set. It must not wait for the
+  // loads just requested (a full __syncthreads would): LDS serves a wave's operations in order, so waiting for
+  // the wave's LDS operations before the barrier is all that the two counter writes need.
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");   // no memory access of the code below moves above the barrier
 
-  float qc[G][2];     // q prescaled by 2^-field_pos of the lane's channel block
+  // q of the lane's two channels, prescaled so that code products of all four channel blocks come out in the
+  // same unit: the field of block ks sits at bit field_pos(ks), the query is scaled by 2^(field_pos(0) - field_pos(ks))
+  // (exact in fp16 for |q| >= 2^-8; smaller values lose bits far below anything the scores resolve)
+  constexpr int kPos0 = field_pos<KB>(0);
+  half2_t qh[G];
   {
-    const float pre = __builtin_ldexpf(1.0f, -field_pos<KB>(lane >> 4));
+    const half_t pre = (half_t)__builtin_ldexpf(1.0f, kPos0 - field_pos<KB>(lane >> 4));
 #pragma unroll
-    for (int hh = 0; hh < G; hh++) {
-      qc[hh][0] = lo_half(qraw[hh]) * pre;
-      qc[hh][1] = hi_half(qraw[hh]) * pre;
-    }
+    for (int hh = 0; hh < G; hh++) qh[hh] = as_half2(qraw[hh]) * half2_t{pre, pre};
   }
 
   const half8_t zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
   const half8_t ones8 = {1, 1, 1, 1, 1, 1, 1, 1};
-  const float c_code = a.scale_log2 * 16777216.0f;   // code products carry 2^-24
+  const float c_code = a.scale_log2 * __builtin_ldexpf(1.0f, 24 - kPos0);   // code products carry 2^(field_pos(0) - 24)
   const float c_plain = a.scale_log2;
 
   float4_t acc[8];
@@ -398,10 +425,10 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
   // raises the per-column reference to cover mx (log2-domain upper estimate of the tile's scores,
   // identical in all lanes of a column pair) and rescales the accumulators accordingly
   auto raise_reference = [&](float mx) {
-    if (__any(mx > mref)) {
+    if (__any(mx > mref + kRefCap)) {
       mx = fmaxf(mx, __shfl_xor(mx, 16));
       mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float mnew = mx > mref ? mx + kRefMargin : mref;
+      const float mnew = mx > mref + kRefCap ? mx + kRefMargin : mref;
       const float f = (mnew == mref) ? 1.0f : fast_exp2(mref - mnew);
       mref = mnew;
       accZ *= f;
@@ -533,7 +560,7 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
       const float sc = wave_sum(__builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, qraw[hh]), __builtin_bit_cast(half2_t, knew_pair), 0.0f, false)) * c_plain;
       s_lane = (h == hh) ? sc : s_lane;
       if constexpr (kSmall) {
-        if (sc > mref_u[hh]) {        // wave-uniform
+        if (sc > mref_u[hh] + kRefCap) {        // wave-uniform
           const float mnew = sc + kRefMargin;
           const float f = fast_exp2(mref_u[hh] - mnew);
           mref_u[hh] = mnew;
@@ -572,14 +599,14 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
     // -- Key side. Lane owns channels 2*lane, 2*lane+1: scale-folded query to LDS, zero-point term by dot product
     float zt[G];
     {
-      const float s0 = lo_half(st.meta[0]), s1 = hi_half(st.meta[0]);
+      const half2_t s2 = as_half2(st.meta[0]);
       const uint32_t kz_pair = st.meta[1];   // a copy: a bit cast applied to the vector element itself reads element 0
 #pragma unroll
       for (int hh = 0; hh < G; hh++) {
         uint32_t hi, lo;
-        split_pair(qc[hh][0] * s0, qc[hh][1] * s1, hi, lo);
-        reinterpret_cast<uint32_t*>(&L.bk[hh][0])[lane] = hi;
-        reinterpret_cast<uint32_t*>(&L.bk[G + hh][0])[lane] = lo;
+        mul_split(qh[hh], s2, hi, lo);
+        reinterpret_cast<uint32_t*>(&L.bk[2 * hh][0])[lane] = hi;
+        reinterpret_cast<uint32_t*>(&L.bk[2 * hh + 1][0])[lane] = lo;
         const float zp = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, qraw[hh]), __builtin_bit_cast(half2_t, kz_pair), 0.0f, false);
         zt[hh] = wave_sum(zp) * c_plain;
       }
@@ -617,18 +644,18 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
       bool over = false;
 #pragma unroll
       for (int hh = 0; hh < G; hh++) {
-        const float2_t sh = *reinterpret_cast<const float2_t*>(&L.s[hh][2 * tp]);
-        const float2_t sl = *reinterpret_cast<const float2_t*>(&L.s[G + hh][2 * tp]);
+        const float2_t sh = *reinterpret_cast<const float2_t*>(&L.s[2 * hh][2 * tp]);
+        const float2_t sl = *reinterpret_cast<const float2_t*>(&L.s[2 * hh + 1][2 * tp]);
         sum0[hh] = sh[0] + sl[0];
         sum1[hh] = sh[1] + sl[1];
-        // score = sum * c_code + zt; it exceeds the reference iff sum > (reference - zt) / c_code
-        over |= fmaxf(sum0[hh], sum1[hh]) > (mref_u[hh] - zt[hh]) * inv_c_code;
+        // score = sum * c_code + zt; it exceeds what the reference allows iff sum > (reference + cap - zt) / c_code
+        over |= fmaxf(sum0[hh], sum1[hh]) > (mref_u[hh] + kRefCap - zt[hh]) * inv_c_code;
       }
       if (__any(over)) {   // rare: raise the reference of the heads that need it and rescale what was accumulated
 #pragma unroll
         for (int hh = 0; hh < G; hh++) {
           const float mx = wave_max(fmaxf(sum0[hh], sum1[hh])) * c_code + zt[hh];
-          if (mx > mref_u[hh]) {          // wave-uniform
+          if (mx > mref_u[hh] + kRefCap) {          // wave-uniform
             const float mnew = mx + kRefMargin;
             const float f = fast_exp2(mref_u[hh] - mnew);      // 0 for the first tile (reference -inf)
             mref_u[hh] = mnew;
@@ -651,8 +678,8 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
         zacc[hh] += p0 * z0 + p1 * z1;
         uint32_t hi, lo;
         split_pair(p0 * s0, p1 * s1, hi, lo);
-        reinterpret_cast<uint32_t*>(&L.bv[g][hh][0])[tp] = hi;
-        reinterpret_cast<uint32_t*>(&L.bv[g][G + hh][0])[tp] = lo;
+        reinterpret_cast<uint32_t*>(&L.bv[g][2 * hh][0])[tp] = hi;
+        reinterpret_cast<uint32_t*>(&L.bv[g][2 * hh + 1][0])[tp] = lo;
       }
     }
     wave_lds_fence();
@@ -670,18 +697,16 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
     wave_lds_fence();   // the next tile's operand writes come after these reads
   };
 
-  // ---- packed tiles: kDepth tiles in flight per wave, taken from the workgroup's counter
-
   auto process_large = [&](const Stage<KB, VB>& st) {
     // -- Key side. Cooperative operand preparation: lane owns channels 2*lane, 2*lane+1.
     {
-      const float s0 = lo_half(st.meta[0]), s1 = hi_half(st.meta[0]);
+      const half2_t s2 = as_half2(st.meta[0]);
 #pragma unroll
       for (int hh = 0; hh < G; hh++) {
         uint32_t hi, lo;
-        split_pair(qc[hh][0] * s0, qc[hh][1] * s1, hi, lo);
-        reinterpret_cast<uint32_t*>(&L.bk[hh][0])[lane] = hi;
-        reinterpret_cast<uint32_t*>(&L.bk[G + hh][0])[lane] = lo;
+        mul_split(qh[hh], s2, hi, lo);
+        reinterpret_cast<uint32_t*>(&L.bk[2 * hh][0])[lane] = hi;
+        reinterpret_cast<uint32_t*>(&L.bk[2 * hh + 1][0])[lane] = lo;
       }
       reinterpret_cast<uint32_t*>(&L.zk[0])[lane] = st.meta[1];
     }
@@ -709,7 +734,7 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
         if (kq == 1) S[0][2] *= (7.0f / 3.0f);
         if (kq == 2) S[1][1] *= (7.0f / 3.0f);
       }
-      zt = Sz[0] * c_plain;
+      zt = Sz[0] * c_plain;          // zero in lo columns (their plain-query operand is zero)
 #pragma unroll
       for (int m = 0; m < 2; m++)
 #pragma unroll
@@ -721,50 +746,52 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
     const float mx_partner = ror8(mx);        // cross-lane read outside any divergent branch: all lanes must take part
     mx = lo_part ? mx_partner : mx;
     raise_reference(mx);
-    const float off_col = zt - mref;          // meaningful in hi lanes: score = sum * c_code + off_col + reference
+    // log2-domain scores against the reference; the zero-point term and the reference enter through the hi column
+    const float off_col = lo_part ? 0.0f : zt - mref;
+#pragma unroll
+    for (int e = 0; e < 8; e++) x[e] = x[e] * c_code + off_col;
 
-    // -- Value side. Raw sums to LDS; lane (tp, g) then owns tokens (2*tp, 2*tp+1) of channel block g:
-    // it finishes the softmax numerators of its two tokens and folds the Value scales into them.
+    // -- Value side. Scores to LDS; lane (tp, g) then owns tokens (2*tp, 2*tp+1) of channel block g.
     if (col_valid) {
       *reinterpret_cast<float4_t*>(&L.s[row][8 * kq]) = float4_t{x[0], x[1], x[2], x[3]};
       *reinterpret_cast<float4_t*>(&L.s[row][8 * kq + 4]) = float4_t{x[4], x[5], x[6], x[7]};
     }
     wave_lds_fence();
     // The four lane groups g would all compute the same numerators; instead group g finishes those of the
-    // heads 4k + g only and hands them to the others through LDS, then every lane folds its own block's
-    // Value scales into all heads.
+    // heads 4k + g only and hands them to the others through LDS as two fp16 terms (the rounded value and what
+    // the rounding left over: together ~22 bits, the same pair enters the Value sums, the zero-point sums and
+    // the denominator).
     {
       const int tp = lane & 15, g = lane >> 4;
-      float offs[G];
-#pragma unroll
-      for (int hh = 0; hh < G; hh++) offs[hh] = uniform_lane(off_col, hh);
 #pragma unroll
       for (int k = 0; k < G / 4; k++) {
         const int hh = 4 * k + g;                                  // differs between the lane groups
-        const float off = g == 0 ? offs[4 * k] : g == 1 ? offs[4 * k + 1] : g == 2 ? offs[4 * k + 2] : offs[4 * k + 3];
-        const float2_t sh = *reinterpret_cast<const float2_t*>(&L.s[hh][2 * tp]);
-        const float2_t sl = *reinterpret_cast<const float2_t*>(&L.s[G + hh][2 * tp]);
-        const float p0 = fast_exp2((sh[0] + sl[0]) * c_code + off);
-        const float p1 = fast_exp2((sh[1] + sl[1]) * c_code + off);
-        *reinterpret_cast<float2_t*>(&L.pp[hh][2 * tp]) = float2_t{p0, p1};
-        uint32_t hi, lo;
-        split_pair(p0, p1, hi, lo);                                // plain numerators: zero-point term and denominator
-        reinterpret_cast<uint32_t*>(&L.pb[hh][0])[tp] = hi;
-        reinterpret_cast<uint32_t*>(&L.pb[G + hh][0])[tp] = lo;
+        const float2_t sh = *reinterpret_cast<const float2_t*>(&L.s[2 * hh][2 * tp]);
+        const float2_t sl = *reinterpret_cast<const float2_t*>(&L.s[2 * hh + 1][2 * tp]);
+        // leading terms rounded to nearest: they are multiplied on their own below, and a truncated leading term
+        // whose remainder's product falls below the fp16 range would bias the sums (plain casts are safe here:
+        // the values come out of the exponential instruction, nothing can be fused into the conversions)
+        const float p0 = fast_exp2(sh[0] + sl[0]), p1 = fast_exp2(sh[1] + sl[1]);
+        const half2_t hv = {(half_t)p0, (half_t)p1};
+        const half2_t lv = {(half_t)(p0 - (float)hv[0]), (half_t)(p1 - (float)hv[1])};
+        reinterpret_cast<uint32_t*>(&L.pq[2 * hh][0])[tp] = as_u32(hv);
+        reinterpret_cast<uint32_t*>(&L.pq[2 * hh + 1][0])[tp] = as_u32(lv);
       }
       reinterpret_cast<uint32_t*>(&L.zv[0][0])[lane] = st.meta[3];
     }
     wave_lds_fence();
     {
       const int tp = lane & 15, g = lane >> 4;
-      const float s0 = lo_half(st.meta[2]), s1 = hi_half(st.meta[2]);
+      const half2_t s2 = as_half2(st.meta[2]);
 #pragma unroll
       for (int hh = 0; hh < G; hh++) {
-        const float2_t pr = *reinterpret_cast<const float2_t*>(&L.pp[hh][2 * tp]);
-        uint32_t hi, lo;
-        split_pair(pr[0] * s0, pr[1] * s1, hi, lo);
-        reinterpret_cast<uint32_t*>(&L.bv[g][hh][0])[tp] = hi;
-        reinterpret_cast<uint32_t*>(&L.bv[g][G + hh][0])[tp] = lo;
+        const half2_t p2 = as_half2(reinterpret_cast<const uint32_t*>(&L.pq[2 * hh][0])[tp]);
+        const half2_t d2 = as_half2(reinterpret_cast<const uint32_t*>(&L.pq[2 * hh + 1][0])[tp]);
+        // (p2 + d2) * s2: exact product of the leading term in two parts, the small term's product folded into the second
+        const half2_t hv = p2 * s2;
+        const half2_t lv = __builtin_elementwise_fma(d2, s2, __builtin_elementwise_fma(p2, s2, -hv));
+        reinterpret_cast<uint32_t*>(&L.bv[g][2 * hh][0])[tp] = as_u32(hv);
+        reinterpret_cast<uint32_t*>(&L.bv[g][2 * hh + 1][0])[tp] = as_u32(lv);
       }
     }
     wave_lds_fence();
@@ -773,7 +800,8 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
       half8_t Bv[4];
 #pragma unroll
       for (int g = 0; g < 4; g++) Bv[g] = *reinterpret_cast<const half8_t*>(&L.bv[g][row][8 * kq]);
-      const half8_t PB = *reinterpret_cast<const half8_t*>(&L.pb[row][8 * kq]);
+      // plain numerators: the column's own row (unused columns: the zero row)
+      const half8_t PB = *reinterpret_cast<const half8_t*>(&L.pq[row][8 * kq]);
       // zero-point term: A rows 0..3 carry the zero-points of channel blocks 0..3, rows 4..15 are ones
       // and accumulate the sum of the numerators
       half8_t z8 = ones8;
@@ -804,7 +832,8 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
     }
   }
 
-  // ---- per-wave result: undo the field scaling, add hi and lo columns, add the zero-point term.
+  // ---- per-wave result (into the wave's own area, whose exchange contents are no longer needed): undo the
+  // field scaling, add hi and lo columns, add the zero-point term.
   // accZ: lanes with kq == 0 hold the zero-point sums of channel blocks 0..3, lanes with kq >= 1 the
   // sum of numerators (any register).
   float zsum[4];
@@ -844,7 +873,7 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
       v += zsum[m >> 1];
       o4[r] = v + ror8(v);
     }
-    if (col < G) *reinterpret_cast<float4_t*>(&R.o[wave][col][16 * m + 4 * kq]) = o4;   // channels 16m + 4kq .. +3
+    if (col < G) *reinterpret_cast<float4_t*>(&s_wave[wave].o[col][16 * m + 4 * kq]) = o4;   // channels 16m + 4kq .. +3
   }
   if (col < G && kq == 0) { R.m[wave][col] = mref; R.l[wave][col] = lsum; }
 
@@ -860,7 +889,7 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
       const float mw = R.m[w][hh];
       const float f = (mw == -INFINITY) ? 0.0f : fast_exp2(mw - M);
       Lsum += R.l[w][hh] * f;
-      O += R.o[w][hh][d] * f;
+      O += s_wave[w].o[hh][d] * f;
     }
   };
   uint16_t* outp = a.out + ((size_t)b * a.Hq + (size_t)jh * G) * kD;
@@ -884,7 +913,7 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
         const float lw = has ? R.l[has ? lane : 0][hh] : 0.0f;
         float o0[kWaves], o1[kWaves];         // requested first: their latency overlaps the weight computation
 #pragma unroll
-        for (int w = 0; w < kWaves; w++) { o0[w] = R.o[w][hh][lane]; o1[w] = R.o[w][hh][lane + kWave]; }
+        for (int w = 0; w < kWaves; w++) { o0[w] = s_wave[w].o[hh][lane]; o1[w] = s_wave[w].o[hh][lane + kWave]; }
         const float M = uniform_lane(row_max(mw), 0);
         const float fw = (mw == -INFINITY) ? 0.0f : fast_exp2(mw - M);
         const float Lsum = uniform_lane(row_sum(lw * fw), 0);
