@@ -265,6 +265,7 @@ int plan_attention(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const uint
   a.k_new = k_new; a.v_new = v_new; a.k_win_w = c->k_win; a.v_win_w = c->v_win; a.new_slot = new_slot;
   a.tiles_cap = c->T_cap / kTile; a.W_cap = c->W_cap; a.n_tiles = c->n_q / kTile; a.n_w = n_w; a.w0 = c->w0;
   a.Hq = sh->Hq; a.Hkv = sh->Hkv; a.n_splits = n_splits;
+  a.items_q = n_items / n_splits; a.items_r = n_items % n_splits;
   const float scale = softmax_scale > 0.0f ? softmax_scale : 1.0f / std::sqrt((float)kD);
   a.scale_log2 = scale * 1.4426950408889634f;
   plan->a = a;

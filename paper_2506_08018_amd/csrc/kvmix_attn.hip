@@ -300,16 +300,16 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
   const bool lo_part = col >= 8;
   const bool col_valid = h < G;
   const int sp = blockIdx.x, u = blockIdx.y;
-  const int b = u / a.Hkv, jh = u % a.Hkv;
   WaveLds<G>& L = s_wave[wave].x;
   uint16_t (&T)[kTile][kTPitch] = s_wave[wave].t;
   const int row = col_valid ? 2 * h + (lo_part ? 1 : 0) : WaveLds<G>::kRows;   // operand row of this lane's column
 
-  // work items of this split: window tiles first, then packed tiles
-  const int n_wt = a.W_cap / kTile;
-  const int n_items = n_wt + a.n_tiles;
-  const int item_begin = (int)(((long long)sp * n_items) / a.n_splits);
-  const int item_end = (int)(((long long)(sp + 1) * n_items) / a.n_splits);
+  // Work items of this split: window tiles first, then packed tiles. Split sp takes items_q items, the first
+  // items_r splits one more (quotient and remainder come from the host: the start of a launch is latency-bound
+  // and integer division takes hundreds of instructions here).
+  const int n_wt = a.W_cap >> 5;
+  const int item_begin = sp * a.items_q + (sp < a.items_r ? sp : a.items_r);
+  const int item_end = item_begin + a.items_q + (sp < a.items_r ? 1 : 0);
   const int win_begin = item_begin < n_wt ? item_begin : n_wt;
   const int win_end = item_end < n_wt ? item_end : n_wt;
   const int p_begin = (item_begin > n_wt ? item_begin : n_wt) - n_wt;
@@ -318,7 +318,7 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
   // ---- everything that has to come from HBM first is requested before anything else is done:
   // the query, then the wave's first window tile or, for the waves without one, its first packed tiles.
   // Packed tiles are claimed from a workgroup counter; the first claims are static (wave order).
-  const uint16_t* qbase = a.q + ((size_t)b * a.Hq + (size_t)jh * G) * kD;
+  const uint16_t* qbase = a.q + (size_t)u * (G * kD);   // heads of unit u = (b, j) are rows (b*Hkv + j)*G .. +G-1 of q and out
   half8_t qB[4];       // plain q as B operand: hi columns hold head h, everything else zero
   uint32_t qraw[G];    // q of channels (2*lane, 2*lane+1) of every head
   {
@@ -364,7 +364,7 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
   // window tile wi of the ring: the Key rows as MFMA A operands (rows = tokens), the Value rows as loaded:
   // 16-byte piece lane + 64*j of the tile's 8 KiB, i.e. token 4*j + kq, channels 8*col .. 8*col+7
   struct WinTile { half8_t Ak[2][4]; u32x4_t Vr[8]; };
-  auto win_first = [&](int wi) { return (wi * kTile - a.w0 + a.W_cap) % a.W_cap; };   // ring rank of the tile's first slot
+  auto win_first = [&](int wi) { const int r = wi * kTile - a.w0; return r < 0 ? r + a.W_cap : r; };   // ring rank of the tile's first slot
   auto win_load = [&](int wi, WinTile& w) {
     const int slot0 = wi * kTile;
     const uint16_t* kw = a.k_win + ((size_t)u * a.W_cap + slot0) * kD;
@@ -892,7 +892,7 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
       O += s_wave[w].o[hh][d] * f;
     }
   };
-  uint16_t* outp = a.out + ((size_t)b * a.Hq + (size_t)jh * G) * kD;
+  uint16_t* outp = a.out + (size_t)u * (G * kD);
 
   if (a.n_splits == 1) {
     if constexpr (G <= 2) {
@@ -993,7 +993,7 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
       }
       M = Mn;
     }
-    a.out[((size_t)b * a.Hq + (size_t)jh * G + hh) * kD + d] = __builtin_bit_cast(uint16_t, (half_t)(O / Lsum));
+    outp[idx] = __builtin_bit_cast(uint16_t, (half_t)(O / Lsum));
   }
   if (tid == 0) __hip_atomic_store(&a.counters[u], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }

@@ -99,6 +99,7 @@ struct AttnArgs {
   uint32_t* counters;     // [units] arrival counters (zero before and after every call)
   int tiles_cap, W_cap, n_tiles, n_w, w0;
   int Hq, Hkv, n_splits;
+  int items_q, items_r;   // (window tiles + packed tiles) divided by n_splits: quotient and remainder
   float scale_log2;       // softmax_scale * log2(e)
 };
 
