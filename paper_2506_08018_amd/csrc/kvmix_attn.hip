@@ -267,11 +267,18 @@ template <int G> struct __attribute__((aligned(16))) WaveLds {
   static constexpr int kRows = 2 * G;                 // index of the zero row (present when columns are unused)
   static constexpr int kZeroRow = kRows < 16 ? 1 : 0;
   uint16_t bk[kRows + kZeroRow][kD + 8];   // scale-folded query [row][channel]
-  uint16_t zk[kD];                         // Key zero-points of the tile
-  float s[2 * G][kTile];                   // scores of the tile in the log2 domain, reference subtracted [row][token] (rows as in bk)
-  uint16_t bv[4][kRows + kZeroRow][kTile + 8];   // scale-folded softmax numerators [channel block][row][token]
-  uint16_t pq[kRows + 1][kTile + 8];       // softmax numerators as two fp16 terms [row][token] (rows as in bk); the last row stays zero
-  uint16_t zv[4][kTile];                   // Value zero-points [channel block][token]
+  // zero-points of the tile: the Key ones [channel] while the Key side is worked on, then the Value ones
+  // [channel block][token] (the same 256 bytes: the Key side is done with them before the Value ones are written)
+  union { uint16_t zk[kD]; uint16_t zv[4][kTile]; };
+  // scores of the tile [row][token] (rows as in bk). Pitch 144 B: the rows are written 16 bytes per lane by
+  // the 16 columns at once, and with a pitch of 128 B all rows would start in the same banks (measured: the two
+  // stores of a tile took as long as all its other LDS traffic together)
+  float s[2 * G][kTile + 4];
+  // scale-folded softmax numerators [channel block][row][token]; the four blocks, written together 4 bytes per
+  // lane, start 64 bytes apart modulo the 256 bytes of one pass over the banks
+  struct BvBlock { uint16_t r[kRows + kZeroRow][kTile + 8]; uint16_t pad[((kRows + kZeroRow) * (kTile + 8) * 2 % 256 == 64) ? 0 : (64 + 256 - (kRows + kZeroRow) * (kTile + 8) * 2 % 256) % 256 / 2]; };
+  BvBlock bv[4];
+  uint16_t pq[kRows + kZeroRow][kTile + 8];   // softmax numerators as two fp16 terms [row][token] (rows as in bk)
 };
 
 template <int G> struct MergeLds {        // per-wave reference maximum and sum of numerators of every head
@@ -288,13 +295,14 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
   constexpr int kTPitch = kD + 8;   // fp16 elements per staged row (272 B: 16-byte aligned rows)
   // and, once the wave has worked through its tiles, its result (a wave's memory is its own: a wave that is
   // done never waits for the others)
-  union WaveArea { WaveLds<G> x; uint16_t t[kTile][kTPitch]; float o[G][kD]; };
+  union WaveArea { WaveLds<G> x; uint16_t t[kTile][kTPitch]; float o[G][kD + 16]; };   // result rows 64 bytes apart modulo a pass over the banks
   __shared__ WaveArea s_wave[kWaves];
   __shared__ MergeLds<G> R;
   __shared__ int s_next;   // next unclaimed packed tile of this workgroup
   __shared__ int s_done;   // waves that have delivered their result
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // said to be uniform: what depends on it alone lives in scalar registers
   const int col = lane & 15, kq = lane >> 4;         // MFMA column / row index, k-quarter
   const int h = col & 7;
   const bool lo_part = col >= 8;
@@ -315,8 +323,7 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
   const int p_begin = (item_begin > n_wt ? item_begin : n_wt) - n_wt;
   const int p_end = (item_end > n_wt ? item_end : n_wt) - n_wt;
 
-  // ---- everything that has to come from HBM first is requested before anything else is done:
-  // the query, then the wave's first window tile or, for the waves without one, its first packed tiles.
+  // ---- the query and the wave's first window tile are requested before anything else is done.
   // Packed tiles are claimed from a workgroup counter; the first claims are static (wave order).
   const uint16_t* qbase = a.q + (size_t)u * (G * kD);   // heads of unit u = (b, j) are rows (b*Hkv + j)*G .. +G-1 of q and out
   half8_t qB[4];       // plain q as B operand: hi columns hold head h, everything else zero
@@ -351,15 +358,6 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
   const bool early = has_packed && wave >= n_win;
   Stage<KB, VB> st[kDepth];
   int it[kDepth];
-  // Past the end a wave re-reads the last tile (cache hit) and skips its work: the load stream and the
-  // loop body stay uniform, which keeps the outstanding-load accounting exact.
-  if (early) {
-#pragma unroll
-    for (int s = 0; s < kDepth; s++) {
-      it[s] = p_begin + s * n_early + (wave - n_win);
-      st[s].load(up, it[s] < p_end ? it[s] : p_end - 1, lane);
-    }
-  }
 
   // window tile wi of the ring: the Key rows as MFMA A operands (rows = tokens), the Value rows as loaded:
   // 16-byte piece lane + 64*j of the tile's 8 KiB, i.e. token 4*j + kq, channels 8*col .. 8*col+7
@@ -513,6 +511,20 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
       st[s].load(up, it[s] < p_end ? it[s] : p_end - 1, lane);
     }
   }
+  }
+  // The waves without a window tile take their first packed tiles by wave order (the counter starts behind
+  // them). They request them only here, not at the kernel's start: tile registers that stay live across the
+  // window code above push the kernel over its register budget, and the spill that follows waits for every
+  // outstanding load; requested here they cost nothing measurable (the start of a launch is bound by the
+  // request rate of the window and query loads anyway).
+  // Past the end a wave re-reads the last tile (cache hit) and skips its work: the load stream and the
+  // loop body stay uniform, which keeps the outstanding-load accounting exact.
+  if (early) {
+#pragma unroll
+    for (int s = 0; s < kDepth; s++) {
+      it[s] = p_begin + s * n_early + (wave - n_win);
+      st[s].load(up, it[s] < p_end ? it[s] : p_end - 1, lane);
+    }
   }
 
   // zero the wave's exchange area (it shared its memory with the staging area): the rows of unused
@@ -678,8 +690,8 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
         zacc[hh] += p0 * z0 + p1 * z1;
         uint32_t hi, lo;
         split_pair(p0 * s0, p1 * s1, hi, lo);
-        reinterpret_cast<uint32_t*>(&L.bv[g][2 * hh][0])[tp] = hi;
-        reinterpret_cast<uint32_t*>(&L.bv[g][2 * hh + 1][0])[tp] = lo;
+        reinterpret_cast<uint32_t*>(&L.bv[g].r[2 * hh][0])[tp] = hi;
+        reinterpret_cast<uint32_t*>(&L.bv[g].r[2 * hh + 1][0])[tp] = lo;
       }
     }
     wave_lds_fence();
@@ -687,7 +699,7 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
       const Codes<VB> vc(st.vc);
       half8_t Bv[4];
 #pragma unroll
-      for (int g = 0; g < 4; g++) Bv[g] = *reinterpret_cast<const half8_t*>(&L.bv[g][row][8 * kq]);
+      for (int g = 0; g < 4; g++) Bv[g] = *reinterpret_cast<const half8_t*>(&L.bv[g].r[row][8 * kq]);
 #pragma unroll
       for (int m = 0; m < 8; m++) {
         acc[m] = mfma16(vc.lo(m), Bv[m >> 1], acc[m]);
@@ -790,8 +802,8 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
         // (p2 + d2) * s2: exact product of the leading term in two parts, the small term's product folded into the second
         const half2_t hv = p2 * s2;
         const half2_t lv = __builtin_elementwise_fma(d2, s2, __builtin_elementwise_fma(p2, s2, -hv));
-        reinterpret_cast<uint32_t*>(&L.bv[g][2 * hh][0])[tp] = as_u32(hv);
-        reinterpret_cast<uint32_t*>(&L.bv[g][2 * hh + 1][0])[tp] = as_u32(lv);
+        reinterpret_cast<uint32_t*>(&L.bv[g].r[2 * hh][0])[tp] = as_u32(hv);
+        reinterpret_cast<uint32_t*>(&L.bv[g].r[2 * hh + 1][0])[tp] = as_u32(lv);
       }
     }
     wave_lds_fence();
@@ -799,7 +811,7 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
       const Codes<VB> vc(st.vc);
       half8_t Bv[4];
 #pragma unroll
-      for (int g = 0; g < 4; g++) Bv[g] = *reinterpret_cast<const half8_t*>(&L.bv[g][row][8 * kq]);
+      for (int g = 0; g < 4; g++) Bv[g] = *reinterpret_cast<const half8_t*>(&L.bv[g].r[row][8 * kq]);
       // plain numerators: the column's own row (unused columns: the zero row)
       const half8_t PB = *reinterpret_cast<const half8_t*>(&L.pq[row][8 * kq]);
       // zero-point term: A rows 0..3 carry the zero-points of channel blocks 0..3, rows 4..15 are ones
