@@ -227,7 +227,7 @@ size_t split_workspace_bytes(int units, int n_splits, int G) {
 
 // Validates an attention call against the cache state `c` (window count n_w) and fills the launch descriptor;
 // launches nothing. With k_new / v_new the newest token of every unit is taken from there (ring slot new_slot,
-// not counted in n_w) and stored into the window by the kernel.
+// counted in n_w) and stored into the window by the kernel.
 int plan_attention(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const uint16_t* q, const kvmix_layer_cache* c, int n_w,
                    const uint16_t* k_new, const uint16_t* v_new, int new_slot,
                    float softmax_scale, uint16_t* out, void* workspace, size_t workspace_bytes, int n_splits, AttnPlan* plan) {
@@ -237,7 +237,7 @@ int plan_attention(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const uint
   if (!aligned16(q) || !aligned16(out)) return KVMIX_ERR_ALIGN;
   st = check_cache(cfg, c, false);
   if (st) return st;
-  if (c->n_q + n_w + (new_slot >= 0 ? 1 : 0) < 1 || n_w < 0 || n_w > c->W_cap) return KVMIX_ERR_BAD_SHAPE;
+  if (c->n_q + n_w < 1 || n_w < 0 || n_w > c->W_cap) return KVMIX_ERR_BAD_SHAPE;
   const int units = sh->B * sh->Hkv, G = sh->Hq / sh->Hkv;
   const int n_items = c->W_cap / kTile + c->n_q / kTile;
   if (n_splits < 0 || n_splits > max_splits(sh)) return KVMIX_ERR_BAD_SHAPE;
@@ -367,15 +367,39 @@ int kvmix_decode_step(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const u
   AttnPlan plan;
   const bool flush = cfg->k_bits != 16 && c->n_w + 1 == cfg->window + kTile;
   if (flush) {
-    // The 32 oldest window tokens move to the packed part before the attention reads them: append, quantize-pack,
-    // then attention. Every check of all three is made first, the attention's against the counters as the append
-    // will leave them, so that a failing call launches nothing and leaves the counters alone.
+    // The 32 oldest window tokens move to the packed part before the attention reads them. Every check is made
+    // first, the attention's against the counters as the flush will leave them, so that a failing call launches
+    // nothing and leaves the counters alone.
     st = check_cache(cfg, c, true);
     if (st) return st;
     if (c->n_q + kTile > c->T_cap || c->W_cap < cfg->window + kTile) return KVMIX_ERR_BAD_SHAPE;
     if (!aligned16(k_new) || !aligned16(v_new)) return KVMIX_ERR_ALIGN;
     kvmix_layer_cache after = *c;
     after.n_q += kTile; after.n_w = c->n_w + 1 - kTile; after.w0 = (c->w0 + kTile) % c->W_cap;
+    if (cfg->window >= kTile) {
+      // The new token is not among the 32 oldest: quantize-and-pack them straight from the ring (one launch), then
+      // the attention launch with the append inside, as on every other step.
+      const int slot = (c->w0 + c->n_w) % c->W_cap;
+      st = plan_attention(sh, cfg, q, &after, after.n_w, k_new, v_new, slot, softmax_scale, out, workspace, workspace_bytes, n_splits, &plan);
+      if (st) return st;
+      const int W = c->W_cap;
+      QuantArgs qa{};
+      qa.k = c->k_win + (size_t)c->w0 * kD;
+      qa.v = c->v_win + (size_t)c->w0 * kD;
+      qa.k_tok = kD; qa.k_unit_b = (int64_t)sh->Hkv * W * kD; qa.k_unit_h = (int64_t)W * kD;
+      qa.v_tok = kD; qa.v_unit_b = (int64_t)sh->Hkv * W * kD; qa.v_unit_h = (int64_t)W * kD;
+      fill_quant_dst(qa, c);
+      qa.tile0 = c->n_q / kTile;
+      qa.Hkv = sh->Hkv;
+      const hipError_t e = launch_quantize_pack(qa, cfg->k_bits, cfg->v_bits, 1, sh->B * sh->Hkv, (hipStream_t)stream);
+      if (e != hipSuccess) return hip_fail(e);
+      c->n_q = after.n_q; c->w0 = after.w0; c->n_w = after.n_w - 1;   // the flush is done; the append follows
+      st = launch_plan(plan, stream);
+      if (st) return st;
+      c->n_w += 1;
+      return KVMIX_OK;
+    }
+    // window length 0: the new token is itself among the 32 that are flushed; append, quantize-pack, attention
     st = plan_attention(sh, cfg, q, &after, after.n_w, nullptr, nullptr, -1, softmax_scale, out, workspace, workspace_bytes, n_splits, &plan);
     if (st) return st;
     st = kvmix_append(sh, cfg, k_new, v_new, c, stream);
@@ -388,8 +412,8 @@ int kvmix_decode_step(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const u
   if (cfg->k_bits != 16 && c->W_cap < cfg->window + kTile) return KVMIX_ERR_BAD_SHAPE;
   if (!aligned16(k_new) || !aligned16(v_new)) return KVMIX_ERR_ALIGN;
   const int slot = (c->w0 + c->n_w) % c->W_cap;
-  // the kernel's window count excludes the new token: it is added as a term of its own (and stored)
-  st = plan_attention(sh, cfg, q, c, c->n_w, k_new, v_new, slot, softmax_scale, out, workspace, workspace_bytes, n_splits, &plan);
+  // the kernel's window count includes the new token: it is read from k_new / v_new in place of its ring row (and stored)
+  st = plan_attention(sh, cfg, q, c, c->n_w + 1, k_new, v_new, slot, softmax_scale, out, workspace, workspace_bytes, n_splits, &plan);
   if (st) return st;
   st = launch_plan(plan, stream);
   if (st) return st;

@@ -340,15 +340,11 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
     for (int hh = 0; hh < G; hh++) qraw[hh] = reinterpret_cast<const uint32_t*>(qbase + (size_t)hh * kD)[lane];
   }
 
-  // Fused append: the newest token of the unit is not in the window arrays yet (the kernel's n_w does not
-  // count it; its ring slot is masked like any slot past the end). One wave of the unit's first split adds
-  // its term to the running softmax by hand and stores it into the window for the steps to come.
-  const bool extra = a.new_slot >= 0 && sp == 0 && wave == kWaves - 1;   // wave-uniform
-  uint32_t knew_pair = 0, vnew_pair = 0;     // channels 2*lane, 2*lane+1 of the new Key / Value row, requested now
-  if (extra) {
-    knew_pair = reinterpret_cast<const uint32_t*>(a.k_new + (size_t)u * kD)[lane];
-    vnew_pair = reinterpret_cast<const uint32_t*>(a.v_new + (size_t)u * kD)[lane];
-  }
+  // Fused append: the newest token of the unit is not in the window arrays yet. The wave that takes the window
+  // tile of its ring slot reads that one row from k_new / v_new instead of the ring, treats it like any other
+  // row of the tile (the host counts it in n_w) and stores it into the ring for the steps to come.
+  const int new_tile = a.new_slot >= 0 ? (a.new_slot >> 5) : -1;
+  const int new_tau = a.new_slot & 31;
 
   constexpr uint32_t kRecBytes = (uint32_t)(record_words(KB, VB) * 4);
   const rsrc_t up = make_rsrc(reinterpret_cast<const char*>(a.packed) + (size_t)u * a.tiles_cap * kRecBytes, (uint32_t)a.tiles_cap * kRecBytes);
@@ -366,11 +362,14 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
   auto win_load = [&](int wi, WinTile& w) {
     const int slot0 = wi * kTile;
     const uint16_t* kw = a.k_win + ((size_t)u * a.W_cap + slot0) * kD;
+    const uint16_t* kn = a.k_new + (size_t)u * kD;
+    const bool has_new = wi == new_tile;      // wave-uniform
 #pragma unroll
     for (int m = 0; m < 2; m++) {
       const int tau = 8 * (col >> 2) + 4 * m + (col & 3);   // row `col` of M-tile m
+      const uint16_t* rowp = (has_new && tau == new_tau) ? kn : kw + (size_t)tau * kD;
 #pragma unroll
-      for (int ks = 0; ks < 4; ks++) w.Ak[m][ks] = *reinterpret_cast<const half8_t*>(kw + (size_t)tau * kD + 32 * ks + 8 * kq);
+      for (int ks = 0; ks < 4; ks++) w.Ak[m][ks] = *reinterpret_cast<const half8_t*>(rowp + 32 * ks + 8 * kq);
     }
   };
   // The Value rows are requested only when the Key rows have been consumed: fewer registers in flight (no
@@ -378,8 +377,33 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
   // (measured 0.3-0.4 us per launch against requesting both at the start).
   auto win_load_v = [&](int wi, WinTile& w) {
     const uint16_t* vw = a.v_win + ((size_t)u * a.W_cap + wi * kTile) * kD;
+    const uint16_t* vn = a.v_new + (size_t)u * kD;
+    const bool has_new = wi == new_tile;
 #pragma unroll
-    for (int j = 0; j < 8; j++) w.Vr[j] = *reinterpret_cast<const u32x4_t*>(vw + (size_t)(4 * j + kq) * kD + 8 * col);
+    for (int j = 0; j < 8; j++) {
+      const uint16_t* rowp = (has_new && 4 * j + kq == new_tau) ? vn : vw + (size_t)(4 * j + kq) * kD;
+      w.Vr[j] = *reinterpret_cast<const u32x4_t*>(rowp + 8 * col);
+    }
+  };
+  // the append itself: the lanes that hold pieces of the new row store them into its ring slot
+  auto store_new_k = [&](int wi, const WinTile& w) {
+    if (wi != new_tile) return;
+    uint16_t* dst = a.k_win_w + ((size_t)u * a.W_cap + a.new_slot) * kD;
+#pragma unroll
+    for (int m = 0; m < 2; m++) {
+      const int tau = 8 * (col >> 2) + 4 * m + (col & 3);
+      if (tau == new_tau) {
+#pragma unroll
+        for (int ks = 0; ks < 4; ks++) *reinterpret_cast<half8_t*>(dst + 32 * ks + 8 * kq) = w.Ak[m][ks];
+      }
+    }
+  };
+  auto store_new_v = [&](int wi, const WinTile& w) {
+    if (wi != new_tile) return;
+    uint16_t* dst = a.v_win_w + ((size_t)u * a.W_cap + a.new_slot) * kD;
+#pragma unroll
+    for (int j = 0; j < 8; j++)
+      if (4 * j + kq == new_tau) *reinterpret_cast<u32x4_t*>(dst + 8 * col) = w.Vr[j];
   };
   WinTile wt;
   int wi = win_begin + wave;
@@ -463,11 +487,13 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
     for (int m = 0; m < 2; m++)
 #pragma unroll
       for (int ks = 0; ks < 4; ks++) S[m] = mfma16(Ak[m][ks], qB[ks], S[m]);
+    store_new_k(wi, wt);
     win_load_v(wi, wt);
     // Value rows into the staging area as loaded (their registers are free again before the softmax). Rows
     // 16..31 swap neighbouring 32-byte blocks, so that the lanes of different kq read from different banks.
 #pragma unroll
     for (int j = 0; j < 8; j++) *reinterpret_cast<u32x4_t*>(&T[4 * j + kq][8 * (col ^ (j >= 4 ? 2 : 0))]) = wt.Vr[j];
+    store_new_v(wi, wt);
     float x[8], p[8];
 #pragma unroll
     for (int m = 0; m < 2; m++)
@@ -552,60 +578,6 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
     }
   }
   const float inv_c_code = 1.0f / c_code;
-
-  // ---- the token that is being appended (see above): score by packed dot products and a wave sum, then its
-  // term of the running softmax in the accumulators' units (code domain: 2^(field position - 24))
-  if (extra) {
-    // the append itself: both rows are in registers, one 4-byte store per lane and row
-    reinterpret_cast<uint32_t*>(a.k_win_w + ((size_t)u * a.W_cap + a.new_slot) * kD)[lane] = knew_pair;
-    reinterpret_cast<uint32_t*>(a.v_win_w + ((size_t)u * a.W_cap + a.new_slot) * kD)[lane] = vnew_pair;
-    // the Value row in the order of the accumulators (channels 16*m + 4*kq .. +3 per lane), through 256 bytes of
-    // the exchange area that the next tile overwrites anyway
-    reinterpret_cast<uint32_t*>(&L.zv[0][0])[lane] = vnew_pair;
-    wave_lds_fence();
-    u32x2_t vnew[8];
-#pragma unroll
-    for (int m = 0; m < 8; m++) vnew[m] = *reinterpret_cast<const u32x2_t*>(&L.zv[0][0] + 16 * m + 4 * kq);
-    float s_lane = -INFINITY;      // the score of the lane's head, log2 domain
-#pragma unroll
-    for (int hh = 0; hh < G; hh++) {
-      const float sc = wave_sum(__builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, qraw[hh]), __builtin_bit_cast(half2_t, knew_pair), 0.0f, false)) * c_plain;
-      s_lane = (h == hh) ? sc : s_lane;
-      if constexpr (kSmall) {
-        if (sc > mref_u[hh] + kRefCap) {        // wave-uniform
-          const float mnew = sc + kRefMargin;
-          const float f = fast_exp2(mref_u[hh] - mnew);
-          mref_u[hh] = mnew;
-          lacc[hh] *= f; zacc[hh] *= f;
-          if (h == hh) {
-            mref = mnew;
-            lwin *= f;
-#pragma unroll
-            for (int m = 0; m < 8; m++) acc[m] *= f;
-          }
-        }
-      }
-    }
-    if constexpr (!kSmall) raise_reference(s_lane);
-    const float pn = (col_valid && !lo_part) ? fast_exp2(s_lane - mref) : 0.0f;
-    if constexpr (kSmall) lwin += pn;                    // every lane of a hi column carries the column's sum
-    else accZ[0] += (kq == 1) ? pn : 0.0f;               // where the sum of numerators is read from at the end
-#pragma unroll
-    for (int m = 0; m < 8; m++) {
-      const float unit = __builtin_ldexpf(1.0f, field_pos<VB>(m & 3) - 24);
-#pragma unroll
-      for (int r = 0; r < 4; r++) {
-        const uint32_t w = vnew[m][r >> 1];
-        float v = (r & 1) ? hi_half(w) : lo_half(w);
-        if constexpr (VB == 3) {   // the final 7/3 step factor of channels 10 / 21 applies to codes only
-          const int dd = 16 * (m & 1) + 4 * kq + r;
-          if (dd == 10 || dd == 21) v *= (3.0f / 7.0f);
-        }
-        acc[m][r] += pn * v * unit;
-      }
-    }
-    wave_lds_fence();   // the row has been read before the first tile's operands are written
-  }
 
   auto process_small = [&](const Stage<KB, VB>& st) {
     // -- Key side. Lane owns channels 2*lane, 2*lane+1: scale-folded query to LDS, zero-point term by dot product

@@ -90,8 +90,8 @@ struct AttnArgs {
   const uint16_t* q; uint16_t* out;
   const uint32_t* packed;
   const uint16_t* k_win; const uint16_t* v_win;
-  // fused append: the newest token of every unit ([units][128] each) is not in the window arrays yet and
-  // not counted in n_w; one wave per unit adds its term and stores it into ring slot new_slot
+  // fused append: the newest token of every unit ([units][128] each) is not in the window arrays yet but counted
+  // in n_w; the wave that takes the window tile of ring slot new_slot reads it from here and stores it
   const uint16_t* k_new; const uint16_t* v_new;
   uint16_t* k_win_w; uint16_t* v_win_w;
   int new_slot;           // -1: nothing to append

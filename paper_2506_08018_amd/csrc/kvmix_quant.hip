@@ -116,8 +116,8 @@ template <int KB, int VB>
 __global__ __launch_bounds__(128) void quantize_pack_kernel(QuantArgs a) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int kq = lane >> 4, j = (lane >> 2) & 3, q = lane & 3;
-  const int tile_in = blockIdx.x, u = blockIdx.y;
-  const int b = u / a.Hkv, jh = u % a.Hkv;
+  const int tile_in = blockIdx.x, jh = blockIdx.y, b = blockIdx.z;   // no integer division at the start of a short kernel
+  const int u = b * a.Hkv + jh;
   uint32_t* rec = a.packed + ((size_t)u * a.tiles_cap + (size_t)(a.tile0 + tile_in)) * record_words(KB, VB);
   uint32_t hi[16];
 #pragma unroll
@@ -341,7 +341,7 @@ hipError_t launch_qp(const QuantArgs& a, dim3 grid, hipStream_t s) {
 hipError_t launch_quantize_pack(const QuantArgs& a, int k_bits, int v_bits,
                                 int n_tiles, int units, hipStream_t s) {
   if (n_tiles == 0 || units == 0) return hipSuccess;
-  const dim3 grid(n_tiles, units);
+  const dim3 grid(n_tiles, a.Hkv, units / a.Hkv);
   switch (k_bits * 10 + v_bits) {
     case 11: return launch_qp<1, 1>(a, grid, s);
     case 12: return launch_qp<1, 2>(a, grid, s);
