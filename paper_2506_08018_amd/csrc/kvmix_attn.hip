@@ -199,8 +199,11 @@ template <> struct Codes<2> {
 template <> struct Codes<3> {
   u32x4_t wa, wb; u32x2_t hs[4];
   __device__ __forceinline__ explicit Codes(const Raw<3>& r) : wa(r.w << 2), wb(r.w >> 6) { shift_hi_plane(r.h, hs); }
-  __device__ __forceinline__ half8_t lo(int slot) const { return unpack2(wa, wb, slot); }
-  __device__ __forceinline__ half8_t hi(int slot) const { return unpack1(hs, slot); }
+  // the 2-bit field with the plane's bit right above it: one 3-bit field, the subnormal (or, with the bit at
+  // position 10, smallest normal) fp16 number code * 2^(pos - 24)
+  __device__ __forceinline__ half8_t lo(int slot) const {
+    return as_half8(__builtin_bit_cast(u32x4_t, unpack2(wa, wb, slot)) | __builtin_bit_cast(u32x4_t, unpack1(hs, slot)));
+  }
 };
 template <> struct Codes<4> {
   u32x4_t wa[2], wb[2];
@@ -607,7 +610,6 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
 #pragma unroll
         for (int ks = 0; ks < 4; ks++) {
           S[m] = mfma16(kc.lo(ks + 4 * m), Bk[ks], S[m]);
-          if constexpr (KB == 3) S[m] = mfma16(kc.hi(ks + 4 * m), Bk[ks], S[m]);
         }
       if constexpr (KB == 3) {   // tokens 10 and 21 of the group step by s*7/3
         if (kq == 1) S[0][2] *= (7.0f / 3.0f);
@@ -675,7 +677,6 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
 #pragma unroll
       for (int m = 0; m < 8; m++) {
         acc[m] = mfma16(vc.lo(m), Bv[m >> 1], acc[m]);
-        if constexpr (VB == 3) acc[m] = mfma16(vc.hi(m), Bv[m >> 1], acc[m]);
       }
     }
     wave_lds_fence();   // the next tile's operand writes come after these reads
@@ -712,7 +713,6 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
 #pragma unroll
         for (int ks = 0; ks < 4; ks++) {
           S[m] = mfma16(kc.lo(ks + 4 * m), Bk[ks], S[m]);
-          if constexpr (KB == 3) S[m] = mfma16(kc.hi(ks + 4 * m), Bk[ks], S[m]);
         }
       if constexpr (KB == 3) {   // tokens 10 and 21 of the group step by s*7/3
         if (kq == 1) S[0][2] *= (7.0f / 3.0f);
@@ -747,15 +747,23 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
     // the denominator).
     {
       const int tp = lane & 15, g = lane >> 4;
+      // (all reads of a step are issued before its first write: the compiler does not move LDS reads across LDS
+      // writes through pointers of the same type, and one read at a time costs an LDS round trip each)
+      constexpr int kShare = G / 4 > 0 ? G / 4 : 1;   // (the function is only used with groups of 4 or 8 heads)
+      float2_t sh[kShare], sl[kShare];
 #pragma unroll
       for (int k = 0; k < G / 4; k++) {
         const int hh = 4 * k + g;                                  // differs between the lane groups
-        const float2_t sh = *reinterpret_cast<const float2_t*>(&L.s[2 * hh][2 * tp]);
-        const float2_t sl = *reinterpret_cast<const float2_t*>(&L.s[2 * hh + 1][2 * tp]);
+        sh[k] = *reinterpret_cast<const float2_t*>(&L.s[2 * hh][2 * tp]);
+        sl[k] = *reinterpret_cast<const float2_t*>(&L.s[2 * hh + 1][2 * tp]);
+      }
+#pragma unroll
+      for (int k = 0; k < G / 4; k++) {
+        const int hh = 4 * k + g;
         // leading terms rounded to nearest: they are multiplied on their own below, and a truncated leading term
         // whose remainder's product falls below the fp16 range would bias the sums (plain casts are safe here:
         // the values come out of the exponential instruction, nothing can be fused into the conversions)
-        const float p0 = fast_exp2(sh[0] + sl[0]), p1 = fast_exp2(sh[1] + sl[1]);
+        const float p0 = fast_exp2(sh[k][0] + sl[k][0]), p1 = fast_exp2(sh[k][1] + sl[k][1]);
         const half2_t hv = {(half_t)p0, (half_t)p1};
         const half2_t lv = {(half_t)(p0 - (float)hv[0]), (half_t)(p1 - (float)hv[1])};
         reinterpret_cast<uint32_t*>(&L.pq[2 * hh][0])[tp] = as_u32(hv);
@@ -767,10 +775,15 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
     {
       const int tp = lane & 15, g = lane >> 4;
       const half2_t s2 = as_half2(st.meta[2]);
+      uint32_t pw[G], dw[G];
 #pragma unroll
       for (int hh = 0; hh < G; hh++) {
-        const half2_t p2 = as_half2(reinterpret_cast<const uint32_t*>(&L.pq[2 * hh][0])[tp]);
-        const half2_t d2 = as_half2(reinterpret_cast<const uint32_t*>(&L.pq[2 * hh + 1][0])[tp]);
+        pw[hh] = reinterpret_cast<const uint32_t*>(&L.pq[2 * hh][0])[tp];
+        dw[hh] = reinterpret_cast<const uint32_t*>(&L.pq[2 * hh + 1][0])[tp];
+      }
+#pragma unroll
+      for (int hh = 0; hh < G; hh++) {
+        const half2_t p2 = as_half2(pw[hh]), d2 = as_half2(dw[hh]);
         // (p2 + d2) * s2: exact product of the leading term in two parts, the small term's product folded into the second
         const half2_t hv = p2 * s2;
         const half2_t lv = __builtin_elementwise_fma(d2, s2, __builtin_elementwise_fma(p2, s2, -hv));
@@ -794,7 +807,6 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
 #pragma unroll
       for (int m = 0; m < 8; m++) {
         acc[m] = mfma16(vc.lo(m), Bv[m >> 1], acc[m]);
-        if constexpr (VB == 3) acc[m] = mfma16(vc.hi(m), Bv[m >> 1], acc[m]);
       }
     }
     wave_lds_fence();   // the next tile's operand writes come after these reads
