@@ -210,21 +210,26 @@ int kvmix_decode_attn_static(const kvmix_shape* shape, const kvmix_layer_cfg* cf
                              const kvmix_layer_cache* cache, float softmax_scale, uint16_t* out,
                              int n_splits, void* stream);
 
-/* kvmix_append for n_tokens consecutive new tokens per sequence (chunked prefill, speculative decoding): exactly
- * n_tokens calls of kvmix_append in a row, with as many flushes of 32 tokens as fall due. Element (b, j, i, d)
- * of k_new / v_new is at b*batch_stride + j*head_stride + i*token_stride + d (strides in elements,
- * token_stride >= 128). Capacity (T_cap, W_cap) is checked for the whole call before anything is launched. */
+/* kvmix_append for n_tokens consecutive new tokens per sequence (chunked prefill, speculative decoding): the same
+ * counters, tile records and live window tokens as n_tokens calls of kvmix_append in a row, in at most two
+ * launches: one quantize-and-pack launch over all tiles that fall due (their tokens are read from the ring or
+ * straight from k_new / v_new: Sec. 3.4 item 1, new states are quantized and joined to the cache without a pass of
+ * their own through memory), then one copy of the new tokens that stay in the window. Element (b, j, i, d)
+ * of k_new / v_new is at b*batch_stride + j*head_stride + i*token_stride + d (strides in elements, multiples of 8,
+ * token_stride >= 128; pointers 16-byte aligned). Capacity (T_cap, W_cap) is checked for the whole call before
+ * anything is launched. Ring slots outside the n_w live tokens are unspecified afterwards. */
 int kvmix_append_tokens(const kvmix_shape* shape, const kvmix_layer_cfg* cfg,
                         const uint16_t* k_new, const uint16_t* v_new,
                         int64_t token_stride, int64_t head_stride, int64_t batch_stride, int n_tokens,
                         kvmix_layer_cache* cache, void* stream);
 
-/* One decode step of a layer: kvmix_append followed by kvmix_decode_attn, same arguments and the same
- * result. Unless the append makes the window overflow (then the two calls are made as they are), the
- * append is done inside the attention launch: the workgroup that reads the window tile of the new slot
- * takes the token from k_new / v_new and stores it into the window (Sec. 3.4 item 1 in spirit: no separate
- * pass over the cache for the new token). Updates n_q, n_w, w0 in *cache (host). k_new, v_new must stay
- * valid until the launch has run. */
+/* One decode step of a layer: kvmix_append followed by kvmix_decode_attn, same arguments and the same result.
+ * The append is done inside the attention launch: the wave that reads the window tile of the new slot takes
+ * that row from k_new / v_new and stores it into the window (Sec. 3.4 item 1 in spirit: no separate pass over
+ * the cache for the new token). On the step where the window overflows one quantize-and-pack launch over the 32
+ * oldest window tokens goes first (with window == 0 the new token is one of them: append, pack, then a plain
+ * attention launch). Updates n_q, n_w, w0 in *cache (host). k_new, v_new (16-byte aligned) must stay valid until
+ * the launches have run. */
 int kvmix_decode_step(const kvmix_shape* shape, const kvmix_layer_cfg* cfg,
                       const uint16_t* k_new, const uint16_t* v_new, const uint16_t* q,
                       kvmix_layer_cache* cache, float softmax_scale, uint16_t* out,

@@ -143,6 +143,7 @@ int kvmix_quantize_pack(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const
   a.k = k_fp16; a.v = v_fp16;
   a.k_tok = token_stride; a.k_unit_b = batch_stride; a.k_unit_h = head_stride;
   a.v_tok = token_stride; a.v_unit_b = batch_stride; a.v_unit_h = head_stride;
+  a.n_ring = 0; a.W_cap = 1;
   fill_quant_dst(a, c);
   a.tile0 = t0 / kTile;
   a.Hkv = sh->Hkv;
@@ -161,6 +162,7 @@ int kvmix_append_tokens(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const
   if (st) return st;
   if (n_tokens < 0) return KVMIX_ERR_BAD_SHAPE;
   if (token_stride < kD || head_stride < 0 || batch_stride < 0) return KVMIX_ERR_ALIGN;
+  if (packed && (!aligned16(k_new) || !aligned16(v_new) || token_stride % 8 || head_stride % 8 || batch_stride % 8)) return KVMIX_ERR_ALIGN;
   if (packed && c->W_cap < cfg->window + kTile) return KVMIX_ERR_BAD_SHAPE;
   // dry run of the counters: nothing is launched unless everything fits
   {
@@ -174,37 +176,41 @@ int kvmix_append_tokens(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const
       if (n_q + flushes * kTile > c->T_cap) return KVMIX_ERR_BAD_SHAPE;
     }
   }
+  if (n_tokens == 0) return KVMIX_OK;
   const int units = sh->B * sh->Hkv, W = c->W_cap;
-  int done = 0;
-  while (done < n_tokens) {
-    const int room = (packed ? cfg->window + kTile : W) - c->n_w;      // tokens until the window overflows
-    const int chunk = n_tokens - done < room ? n_tokens - done : room;
+  // The old window tokens followed by the new ones form one sequence of m rows; its first 32 F rows leave for the
+  // packed part (F tiles, from the ring or straight from the input: a token that is flushed within this call never
+  // passes through the ring), the rest is the new window. Two launches: the quantizer over the F tiles, then the copy
+  // of the surviving new rows into their ring slots (in this order: a new row may land in the slot of an old one
+  // that the quantizer still has to read).
+  const long long m = (long long)c->n_w + n_tokens;
+  const int F = packed && m >= cfg->window + kTile ? (int)((m - cfg->window) / kTile) : 0;
+  if (F > 0) {
+    QuantArgs a{};
+    a.k = k_new; a.v = v_new;
+    a.k_tok = token_stride; a.k_unit_b = batch_stride; a.k_unit_h = head_stride;
+    a.v_tok = token_stride; a.v_unit_b = batch_stride; a.v_unit_h = head_stride;
+    a.k_ring = c->k_win; a.v_ring = c->v_win; a.n_ring = c->n_w; a.ring_w0 = c->w0; a.W_cap = W;
+    fill_quant_dst(a, c);
+    a.tile0 = c->n_q / kTile;
+    a.Hkv = sh->Hkv;
+    const hipError_t e = launch_quantize_pack(a, cfg->k_bits, cfg->v_bits, F, units, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(e);
+  }
+  const long long first_kept = (long long)F * kTile;                       // first row of the sequence that stays in the window
+  const int i0 = first_kept > c->n_w ? (int)(first_kept - c->n_w) : 0;      // first new token that stays
+  if (i0 < n_tokens) {
     AppendArgs ap{};
-    ap.k_new = k_new + (int64_t)done * token_stride; ap.v_new = v_new + (int64_t)done * token_stride;
+    ap.k_new = k_new + (int64_t)i0 * token_stride; ap.v_new = v_new + (int64_t)i0 * token_stride;
     ap.tok = token_stride; ap.head = head_stride; ap.batch = batch_stride;
     ap.k_win = c->k_win; ap.v_win = c->v_win;
-    ap.W_cap = W; ap.slot = (c->w0 + c->n_w) % W; ap.n = chunk; ap.units = units; ap.Hkv = sh->Hkv;
-    hipError_t e = launch_append(ap, (hipStream_t)stream);
+    ap.W_cap = W; ap.slot = (int)((c->w0 + c->n_w + (long long)i0) % W); ap.n = n_tokens - i0; ap.units = units; ap.Hkv = sh->Hkv;
+    const hipError_t e = launch_append(ap, (hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(e);
-    c->n_w += chunk;
-    done += chunk;
-    if (packed && c->n_w == cfg->window + kTile) {
-      // the oldest 32 tokens are ring slots w0 .. w0+31; same quantizer, destination tile n_q/32
-      QuantArgs a{};
-      a.k = c->k_win + (size_t)c->w0 * kD;
-      a.v = c->v_win + (size_t)c->w0 * kD;
-      a.k_tok = kD; a.k_unit_b = (int64_t)sh->Hkv * W * kD; a.k_unit_h = (int64_t)W * kD;
-      a.v_tok = kD; a.v_unit_b = (int64_t)sh->Hkv * W * kD; a.v_unit_h = (int64_t)W * kD;
-      fill_quant_dst(a, c);
-      a.tile0 = c->n_q / kTile;
-      a.Hkv = sh->Hkv;
-      e = launch_quantize_pack(a, cfg->k_bits, cfg->v_bits, 1, units, (hipStream_t)stream);
-      if (e != hipSuccess) return hip_fail(e);
-      c->n_q += kTile;
-      c->n_w -= kTile;
-      c->w0 = (c->w0 + kTile) % W;
-    }
   }
+  c->n_q += F * kTile;
+  c->w0 = (int)((c->w0 + first_kept) % W);
+  c->n_w = (int)(m - first_kept);
   return KVMIX_OK;
 }
 
@@ -384,10 +390,7 @@ int kvmix_decode_step(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const u
       if (st) return st;
       const int W = c->W_cap;
       QuantArgs qa{};
-      qa.k = c->k_win + (size_t)c->w0 * kD;
-      qa.v = c->v_win + (size_t)c->w0 * kD;
-      qa.k_tok = kD; qa.k_unit_b = (int64_t)sh->Hkv * W * kD; qa.k_unit_h = (int64_t)W * kD;
-      qa.v_tok = kD; qa.v_unit_b = (int64_t)sh->Hkv * W * kD; qa.v_unit_h = (int64_t)W * kD;
+      qa.k_ring = c->k_win; qa.v_ring = c->v_win; qa.n_ring = kTile; qa.ring_w0 = c->w0; qa.W_cap = W;
       fill_quant_dst(qa, c);
       qa.tile0 = c->n_q / kTile;
       qa.Hkv = sh->Hkv;

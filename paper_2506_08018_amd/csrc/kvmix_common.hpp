@@ -65,9 +65,14 @@ __host__ __device__ inline void value_td(int l, int j, int hh, int slot, int& ta
 
 // Launch descriptors filled by the C-ABI layer (host) and passed by value.
 struct QuantArgs {
+  // The token sequence that is quantized: its rows [0, n_ring) are the ring slots (ring_w0 + r) % W_cap of the two
+  // fp16 windows ([units][W_cap][128]), every later row r is row r - n_ring of the input. Tile t takes rows
+  // 32 t .. 32 t + 31.
   const uint16_t* k; const uint16_t* v;
   int64_t k_tok, k_unit_b, k_unit_h;            // Key input: channel stride 1
   int64_t v_tok, v_unit_b, v_unit_h;            // Value input: channel stride 1
+  const uint16_t* k_ring; const uint16_t* v_ring;
+  int n_ring, ring_w0, W_cap;
   uint32_t* packed;
   int tiles_cap;   // tiles per unit in the packed cache
   int tile0;       // first destination tile

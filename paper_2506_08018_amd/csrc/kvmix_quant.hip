@@ -112,6 +112,17 @@ __device__ __forceinline__ void store_words(uint32_t* sec, const uint32_t (&w)[a
 //               fields of slots 2*g, 2*g + 1 from this lane, the other blocks from the quad.
 // The lanes of a quad OR their partial words together (DPP), the 1-bit plane of 3-bit codes also across the
 // two j of a word; each lane then stores a quarter of the words. No LDS.
+// Row r of the sequence a launch quantizes: a ring slot of the window or a row of the input.
+__device__ __forceinline__ const uint16_t* source_row(const uint16_t* ring, const uint16_t* in, int64_t tok, int64_t unit_off,
+                                                      const QuantArgs& a, int u, int r) {
+  if (r < a.n_ring) {
+    int slot = a.ring_w0 + r;
+    if (slot >= a.W_cap) slot -= a.W_cap;
+    return ring + ((size_t)u * a.W_cap + slot) * kD;
+  }
+  return in + unit_off + (int64_t)(r - a.n_ring) * tok;
+}
+
 template <int KB, int VB>
 __global__ __launch_bounds__(128) void quantize_pack_kernel(QuantArgs a) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -124,11 +135,11 @@ __global__ __launch_bounds__(128) void quantize_pack_kernel(QuantArgs a) {
   for (int i = 0; i < 16; i++) hi[i] = 0;
 
   if (wave == 0) {
-    const uint16_t* kin = a.k + b * a.k_unit_b + jh * a.k_unit_h + (int64_t)tile_in * kTile * a.k_tok;
+    const int64_t k_off = b * a.k_unit_b + jh * a.k_unit_h;
     const int d0 = 32 * q + 8 * kq + 2 * j;
     uint32_t xw[kTile];                              // (x[tau][d0], x[tau][d0 + 1])
 #pragma unroll
-    for (int t = 0; t < kTile; t++) xw[t] = *reinterpret_cast<const uint32_t*>(kin + (int64_t)t * a.k_tok + d0);
+    for (int t = 0; t < kTile; t++) xw[t] = *reinterpret_cast<const uint32_t*>(source_row(a.k_ring, a.k, a.k_tok, k_off, a, u, tile_in * kTile + t) + d0);
     half2_t mn2 = as_half2(xw[0]), mx2 = mn2;
 #pragma unroll
     for (int t = 1; t < kTile; t++) {
@@ -182,13 +193,14 @@ __global__ __launch_bounds__(128) void quantize_pack_kernel(QuantArgs a) {
     }
     store_words<KB>(rec + kMetaWords, w, hi, kq, j, q);
   } else {
-    const uint16_t* vin = a.v + b * a.v_unit_b + jh * a.v_unit_h + (int64_t)tile_in * kTile * a.v_tok;
+    const int64_t v_off = b * a.v_unit_b + jh * a.v_unit_h;
     const int tau0 = 8 * kq + 2 * j;
     u32x4_t xr[2][4];                                // rows tau0, tau0 + 1: channels 32*q .. 32*q + 31
 #pragma unroll
     for (int hh = 0; hh < 2; hh++)
 #pragma unroll
-      for (int c = 0; c < 4; c++) xr[hh][c] = *reinterpret_cast<const u32x4_t*>(vin + (int64_t)(tau0 + hh) * a.v_tok + 32 * q + 8 * c);
+      for (int c = 0; c < 4; c++)
+        xr[hh][c] = *reinterpret_cast<const u32x4_t*>(source_row(a.v_ring, a.v, a.v_tok, v_off, a, u, tile_in * kTile + tau0 + hh) + 32 * q + 8 * c);
     GroupParams gp[2];
 #pragma unroll
     for (int hh = 0; hh < 2; hh++) {

@@ -71,6 +71,16 @@ def assert_cache_equal(rc, gc, n_tiles=None):
     assert np.array_equal(got_packed[:, :nt], rc.packed[:, :nt]), "tile records differ outside the decoded fields"
 
 
+def assert_windows_equal(rc, gc):
+    """The live tokens of both fp16 ring windows, bit for bit (slots outside the n_w live ones are unspecified: a
+    token that is quantized within the call that brought it never has to pass through the ring)."""
+    kw, vw = bits_of(gc.k_win, np.uint16).reshape(rc.k_win.shape), bits_of(gc.v_win, np.uint16).reshape(rc.v_win.shape)
+    W = rc.k_win.shape[1]
+    slots = [(rc.w0 + r) % W for r in range(rc.n_w)]
+    assert np.array_equal(kw[:, slots], rc.k_win[:, slots]), "Key window"
+    assert np.array_equal(vw[:, slots], rc.v_win[:, slots]), "Value window"
+
+
 TIGHT_ABS = 1e-4  # accumulation noise floor (fp32 sums, matrix-core product truncation) on top of one fp16 spacing
 
 

@@ -3,7 +3,7 @@ import numpy as np
 import pytest
 
 import kvmix_synth as synth
-from gpu_common import assert_attn_close, assert_cache_equal, bits_of, make_pair, run_attn, t16, u16
+from gpu_common import assert_attn_close, assert_cache_equal, assert_windows_equal, bits_of, make_pair, run_attn, t16, u16
 
 pytestmark = pytest.mark.gpu
 
@@ -155,8 +155,7 @@ def test_append_and_flush_match_oracle(kb, vb, G):
             assert_attn_close(run_attn(gc, shape, cfg, q), want, f"after append {s}")
     torch.cuda.synchronize()
     assert_cache_equal(rc, gc)
-    assert np.array_equal(bits_of(gc.k_win, np.uint16).reshape(rc.k_win.shape), rc.k_win)
-    assert np.array_equal(bits_of(gc.v_win, np.uint16).reshape(rc.v_win.shape), rc.v_win)
+    assert_windows_equal(rc, gc)
 
 
 @pytest.mark.parametrize("kb,vb", [(2, 2), (3, 4), (16, 16)])
@@ -167,11 +166,11 @@ def test_append_tokens_equals_single_appends(kb, vb):
     import paper_2506_08018_amd as kv
     print(f"case append_tokens kb={kb} vb={vb}", flush=True)
     B, Hkv, G, W, T0 = 2, 2, 2, 32, 64 + 5
-    chunks = [1, 7, 32, 45, 100, 3]
+    chunks = [1, 7, 32, 45, 100, 3, 31, 64, 33]
     total = sum(chunks)
     q, k, v = synth.gen_layer_numpy(830, 0, B, Hkv * G, Hkv, T0 + total)
-    W_cap = 64 if kb != 16 else 320
-    _, _, _, rc, gc, shape, cfg = make_pair(B, Hkv * G, Hkv, T0, W, kb, vb, T_cap=320, W_cap=W_cap, q_k_v=(q, k[:, :, :T0], v[:, :, :T0]))
+    W_cap = 64 if kb != 16 else 448
+    _, _, _, rc, gc, shape, cfg = make_pair(B, Hkv * G, Hkv, T0, W, kb, vb, T_cap=448, W_cap=W_cap, q_k_v=(q, k[:, :, :T0], v[:, :, :T0]))
     kt, vt = torch.from_numpy(k).cuda(), torch.from_numpy(v).cuda()
     t = T0
     for n in chunks:
@@ -183,9 +182,7 @@ def test_append_tokens_equals_single_appends(kb, vb):
     torch.cuda.synchronize()
     if kb != 16:
         assert_cache_equal(rc, gc)
-    # window slots that hold live tokens must agree (slots past the live range keep older data on both sides)
-    assert np.array_equal(bits_of(gc.k_win, np.uint16).reshape(rc.k_win.shape), rc.k_win)
-    assert np.array_equal(bits_of(gc.v_win, np.uint16).reshape(rc.v_win.shape), rc.v_win)
+    assert_windows_equal(rc, gc)
     st, want = rc.decode_attn(u16(q))
     assert_attn_close(run_attn(gc, shape, cfg, q), want, "after chunked appends", tight=True)
 
@@ -219,8 +216,32 @@ def test_decode_step_equals_append_then_attention(kb, vb, G, n_splits):
     assert not ws[: 4 * shape.units].any()
     if kb != 16:
         assert_cache_equal(rc, gc)
-    assert np.array_equal(bits_of(gc.k_win, np.uint16).reshape(rc.k_win.shape), rc.k_win)
-    assert np.array_equal(bits_of(gc.v_win, np.uint16).reshape(rc.v_win.shape), rc.v_win)
+    assert_windows_equal(rc, gc)
+
+
+def test_decode_steps_with_window_length_zero():
+    """Window length 0: every 32nd step the appended token is itself among the 32 that are quantized (it never
+    passes through the ring); in between the window holds 1..31 tokens."""
+    import torch
+    import paper_2506_08018_amd as kv
+    print("case decode_step window 0", flush=True)
+    B, Hkv, G, W, T0, steps, kb, vb = 1, 2, 2, 0, 64 + 30, 40, 2, 3
+    q, k, v = synth.gen_layer_numpy(815, 0, B, Hkv * G, Hkv, T0 + steps)
+    _, _, _, rc, gc, shape, cfg = make_pair(B, Hkv * G, Hkv, T0, W, kb, vb, T_cap=160, W_cap=32, q_k_v=(q, k[:, :, :T0], v[:, :, :T0]))
+    assert (gc.n_q, gc.n_w) == (64, 30)
+    kt, vt = torch.from_numpy(k).cuda(), torch.from_numpy(v).cuda()
+    qt = torch.from_numpy(q).cuda()
+    out = torch.zeros_like(qt)
+    for s in range(steps):
+        assert rc.append(u16(k[:, :, T0 + s]), u16(v[:, :, T0 + s])) == 0
+        st, want = rc.decode_attn(u16(q))
+        assert st == 0
+        kv.decode_step(shape, cfg, kt[:, :, T0 + s].contiguous(), vt[:, :, T0 + s].contiguous(), qt, gc, out)
+        torch.cuda.synchronize()
+        assert (gc.n_q, gc.n_w, gc.w0) == (rc.n_q, rc.n_w, rc.w0)
+        assert_attn_close(t16(out), want, f"window 0, step {s} (n_q {gc.n_q}, n_w {gc.n_w})", tight=True)
+    assert_cache_equal(rc, gc)
+    assert_windows_equal(rc, gc)
 
 
 @pytest.mark.parametrize("kb,vb,G", [(2, 2, 1), (3, 4, 4), (4, 2, 8)])
