@@ -22,7 +22,8 @@
  *     besides the last HIP error code. Work is enqueued on `stream` (a hipStream_t passed
  *     as void*, NULL = default stream) and the call returns without synchronizing.
  *   - one "unit" is one (batch b, kv head j) pair, u = b*Hkv + j. Query head h reads kv head
- *     h / G, G = Hq / Hkv (G in {1,2,4,8}).
+ *     h / G, G = Hq / Hkv: 1, 2, 4 or a multiple of 8 up to 512 (multi-query attention: Hkv = 1; a head count
+ *     that is no such multiple is padded by the caller with zero query rows, whose outputs are ignored).
  *   - D = 128 and group = 32 are the only supported head dimension / group size
  *     (the paper's setting, Sec. 4.2).
  *
@@ -113,7 +114,7 @@ typedef enum {
   KVMIX_ERR_NULL = -1,      /* a required pointer is NULL */
   KVMIX_ERR_BAD_BITS = -2,  /* bits not in {1,2,3,4}, or 16 for one of K/V only */
   KVMIX_ERR_BAD_GROUP = -3, /* group != 32 */
-  KVMIX_ERR_BAD_SHAPE = -4, /* D != 128, Hq % Hkv, G not in {1,2,4,8}, counts not multiples of 32, capacity exceeded */
+  KVMIX_ERR_BAD_SHAPE = -4, /* D != 128, Hq % Hkv, G not 1, 2, 4 or a multiple of 8, counts not multiples of 32, capacity exceeded */
   KVMIX_ERR_ALIGN = -5,     /* a pointer is not 16-byte aligned or a stride is not a multiple of 8 elements */
   KVMIX_ERR_WORKSPACE = -6, /* workspace too small */
   KVMIX_ERR_HIP = -7        /* a HIP call failed; see kvmix_last_hip_error() */

@@ -38,7 +38,7 @@ int check_shape_cfg(const kvmix_shape* sh, const kvmix_layer_cfg* cfg) {
   if (sh->group != kTile) return KVMIX_ERR_BAD_GROUP;
   if (sh->D != kD || sh->B < 1 || sh->Hkv < 1 || sh->Hq < 1 || sh->Hq % sh->Hkv) return KVMIX_ERR_BAD_SHAPE;
   const int G = sh->Hq / sh->Hkv;
-  if (G != 1 && G != 2 && G != 4 && G != 8) return KVMIX_ERR_BAD_SHAPE;
+  if (G != 1 && G != 2 && G != 4 && (G % 8 != 0 || G > 512)) return KVMIX_ERR_BAD_SHAPE;
   if ((long long)sh->B * sh->Hkv > 65535) return KVMIX_ERR_BAD_SHAPE;
   const int kb = cfg->k_bits, vb = cfg->v_bits;
   if (kb == 16 || vb == 16) {
@@ -67,8 +67,14 @@ int check_cache(const kvmix_layer_cfg* cfg, const kvmix_layer_cache* c, bool nee
   return KVMIX_OK;
 }
 
+// (unit, block of at most 8 query heads) pairs: each is one workgroup per split
+int out_units(const kvmix_shape* sh) {
+  const int G = sh->Hq / sh->Hkv;
+  return sh->B * sh->Hkv * (G > 8 ? G / 8 : 1);
+}
+
 int max_splits(const kvmix_shape* sh) {
-  const int units = sh->B * sh->Hkv;
+  const int units = out_units(sh);
   int s = 512 / units;
   if (s < 8) s = 8;
   if (s > 64) s = 64;
@@ -123,7 +129,7 @@ int kvmix_workspace_bytes(const kvmix_shape* sh, int T_max, size_t* bytes) {
   if (!bytes) return KVMIX_ERR_NULL;
   if (T_max < 0) return KVMIX_ERR_BAD_SHAPE;
   const size_t units = (size_t)sh->B * sh->Hkv, G = (size_t)(sh->Hq / sh->Hkv);
-  *bytes = counters_bytes((int)units) + units * (size_t)max_splits(sh) * G * (kD + 2) * sizeof(float);
+  *bytes = counters_bytes(out_units(sh)) + units * (size_t)max_splits(sh) * G * (kD + 2) * sizeof(float);
   return KVMIX_OK;
 }
 
@@ -228,7 +234,7 @@ namespace {
 struct AttnPlan { AttnArgs a; int kb, vb, G, units; };
 
 size_t split_workspace_bytes(int units, int n_splits, int G) {
-  return counters_bytes(units) + (size_t)units * n_splits * G * (kD + 2) * sizeof(float);
+  return counters_bytes(units * (G > 8 ? G / 8 : 1)) + (size_t)units * n_splits * G * (kD + 2) * sizeof(float);
 }
 
 // Validates an attention call against the cache state `c` (window count n_w) and fills the launch descriptor;
@@ -251,7 +257,7 @@ int plan_attention(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const uint
     // one workgroup occupies a whole compute unit (LDS): aim at one workgroup per unit, at least 8 tiles each
     const int cus = num_cus();
     if (cus == 0) return hip_fail(hipErrorInvalidDevice);
-    n_splits = cus / units;
+    n_splits = cus / out_units(sh);
     if (n_splits > n_items / 8) n_splits = n_items / 8;
     if (n_splits > max_splits(sh)) n_splits = max_splits(sh);
     if (n_splits < 1) n_splits = 1;
@@ -263,7 +269,7 @@ int plan_attention(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const uint
     if (!aligned16(workspace)) return KVMIX_ERR_ALIGN;
     if (workspace_bytes < split_workspace_bytes(units, n_splits, G)) return KVMIX_ERR_WORKSPACE;
     a.counters = reinterpret_cast<uint32_t*>(workspace);
-    a.part = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) + counters_bytes(units));
+    a.part = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) + counters_bytes(out_units(sh)));
   }
   a.q = q; a.out = out;
   a.packed = c->packed;
@@ -299,9 +305,9 @@ __global__ void clear_words_kernel(uint32_t* p, int n) {
   if (i < n) p[i] = 0u;
 }
 
-// Address of the current device's copy of `scratch`. The first call on a device also clears the arrival
-// counters at the array's start (on `stream`, ahead of the first launch that uses them); afterwards every
-// attention launch leaves them zero again.
+// Address of the current device's copy of `scratch`. The first call on a device also clears the array (the
+// arrival counters sit at its start) on `stream`, ahead of the first launch that uses it; afterwards every
+// attention launch leaves the counters zero again.
 int scratch_address(void** ptr, hipStream_t stream) {
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
@@ -313,8 +319,8 @@ int scratch_address(void** ptr, hipStream_t stream) {
     e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
     if (e != hipSuccess) return hip_fail(e);
     if (!p) return hip_fail(hipErrorInvalidSymbol);
-    constexpr int kCounterWords = 65536;       // units <= 65535
-    clear_words_kernel<<<kCounterWords / 256, 256, 0, stream>>>(reinterpret_cast<uint32_t*>(p), kCounterWords);
+    constexpr int kWords = (int)(kScratchBytes / 4);       // the whole array: the counters sit at its start, however many
+    clear_words_kernel<<<kWords / 256, 256, 0, stream>>>(reinterpret_cast<uint32_t*>(p), kWords);
     e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e);
     g_scratch_ptr[dev] = p;
@@ -357,7 +363,7 @@ int kvmix_decode_attn_static(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, 
     st = scratch_address(&ptr, (hipStream_t)stream);
     if (st) return st;
     plan.a.counters = reinterpret_cast<uint32_t*>(ptr);
-    plan.a.part = reinterpret_cast<float*>(reinterpret_cast<char*>(ptr) + counters_bytes(plan.units));
+    plan.a.part = reinterpret_cast<float*>(reinterpret_cast<char*>(ptr) + counters_bytes(plan.units * (plan.G > 8 ? plan.G / 8 : 1)));
   } else {
     plan.a.counters = nullptr; plan.a.part = nullptr;
   }

@@ -311,6 +311,10 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
   const bool lo_part = col >= 8;
   const bool col_valid = h < G;
   const int sp = blockIdx.x, u = blockIdx.y;
+  // Query groups of more than 8 heads run as blocks of 8 heads in workgroups of their own (grid z): the blocks of
+  // a unit read the same records and window rows at about the same time, so a tile comes from HBM once and from
+  // the caches after that. uo numbers the (unit, head block) pairs: rows uo*8 .. uo*8+7 of q and out.
+  const int uo = u * (int)gridDim.z + (int)blockIdx.z;
   WaveLds<G>& L = s_wave[wave].x;
   uint16_t (&T)[kTile][kTPitch] = s_wave[wave].t;
   const int row = col_valid ? 2 * h + (lo_part ? 1 : 0) : WaveLds<G>::kRows;   // operand row of this lane's column
@@ -328,7 +332,7 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
 
   // ---- the query and the wave's first window tile are requested before anything else is done.
   // Packed tiles are claimed from a workgroup counter; the first claims are static (wave order).
-  const uint16_t* qbase = a.q + (size_t)u * (G * kD);   // heads of unit u = (b, j) are rows (b*Hkv + j)*G .. +G-1 of q and out
+  const uint16_t* qbase = a.q + (size_t)uo * (G * kD);   // heads of unit u = (b, j) are rows (b*Hkv + j)*G .. +G-1 of q and out
   half8_t qB[4];       // plain q as B operand: hi columns hold head h, everything else zero
   uint32_t qraw[G];    // q of channels (2*lane, 2*lane+1) of every head
   {
@@ -888,7 +892,7 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
       O += s_wave[w].o[hh][d] * f;
     }
   };
-  uint16_t* outp = a.out + (size_t)u * (G * kD);
+  uint16_t* outp = a.out + (size_t)uo * (G * kD);
 
   if (a.n_splits == 1) {
     if constexpr (G <= 2) {
@@ -941,7 +945,7 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
     combine(idx, M, Lsum, O);
     // agent-scope stores: written through to the level all XCDs share (no cache-wide flush needed)
     const int hh = idx / kD, d = idx % kD;
-    float* pp = a.part + (((size_t)u * a.n_splits + sp) * G + hh) * (kD + 2);
+    float* pp = a.part + (((size_t)uo * a.n_splits + sp) * G + hh) * (kD + 2);
     if (d == 0) { st_agent(pp, M); st_agent(pp + 1, Lsum); }
     st_agent(pp + 2 + d, O);
   }
@@ -952,14 +956,14 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's partial stores have completed ...
   __syncthreads();                                     // ... and so have those of all waves, before the arrival is counted
   if (tid == 0) {
-    const uint32_t prev = __hip_atomic_fetch_add(&a.counters[u], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const uint32_t prev = __hip_atomic_fetch_add(&a.counters[uo], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     s_done = (prev == (uint32_t)a.n_splits - 1u);   // reused as the "last workgroup" flag
   }
   __syncthreads();
   if (!s_done) return;
   for (int idx = tid; idx < G * kD; idx += kThreads) {
     const int hh = idx / kD, d = idx % kD;
-    const float* base = a.part + ((size_t)u * a.n_splits * G + hh) * (kD + 2);
+    const float* base = a.part + ((size_t)uo * a.n_splits * G + hh) * (kD + 2);
     const size_t stride = (size_t)G * (kD + 2);
     // one pass, kMergeBatch splits per round trip: the loads of a batch are issued together
     float M = -INFINITY, Lsum = 0.0f, O = 0.0f;
@@ -991,7 +995,7 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
     }
     outp[idx] = __builtin_bit_cast(uint16_t, (half_t)(O / Lsum));
   }
-  if (tid == 0) __hip_atomic_store(&a.counters[u], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (tid == 0) __hip_atomic_store(&a.counters[uo], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 template <int KB, int VB>
@@ -1009,7 +1013,9 @@ hipError_t launch_g(const AttnArgs& a, int G, dim3 grid, hipStream_t s) {
 }  // namespace
 
 hipError_t launch_decode_attn(const AttnArgs& a, int k_bits, int v_bits, int G, int units, hipStream_t s) {
-  const dim3 grid(a.n_splits, units);
+  const int head_blocks = G > 8 ? G / 8 : 1;
+  if (G > 8) G = 8;
+  const dim3 grid(a.n_splits, units, head_blocks);
   switch (k_bits * 10 + v_bits) {
     case 11: return launch_g<1, 1>(a, G, grid, s);
     case 12: return launch_g<1, 2>(a, G, grid, s);

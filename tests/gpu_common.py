@@ -112,5 +112,5 @@ def run_attn(gc, shape, cfg, q, n_splits=0, softmax_scale=0.0):
     ws = torch.zeros(kv.workspace_bytes(shape, gc.T_cap), dtype=torch.uint8, device="cuda")
     kv.decode_attn(shape, cfg, qt, gc, out, ws, softmax_scale=softmax_scale, n_splits=n_splits)
     torch.cuda.synchronize()
-    assert not ws[: 4 * shape.units].any(), "arrival counters not reset"
+    assert not ws[: 4 * shape.units * max(1, shape.Hq // shape.Hkv // 8)].any(), "arrival counters not reset"
     return t16(out)

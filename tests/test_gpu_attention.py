@@ -219,6 +219,35 @@ def test_decode_step_equals_append_then_attention(kb, vb, G, n_splits):
     assert_windows_equal(rc, gc)
 
 
+@pytest.mark.parametrize("Hq,Hkv,kb,vb,n_splits", [(72, 1, 2, 2, 0), (16, 1, 3, 4, 2), (64, 2, 2, 4, 1), (24, 1, 4, 3, 3)])
+def test_multi_query_and_large_groups(Hq, Hkv, kb, vb, n_splits):
+    """Multi-query attention and groups of more than 8 query heads per kv head (a 71-head model with one kv head,
+    padded to 72 = 9 blocks of 8): every head block of a unit reads the same packed tiles and window."""
+    import torch
+    import paper_2506_08018_amd as kv
+    print(f"case mqa Hq={Hq} Hkv={Hkv} kb={kb} vb={vb} splits={n_splits}", flush=True)
+    B, T, W = 2, 32 * 22 + 13, 32
+    q, k, v, rc, gc, shape, cfg = make_pair(B, Hq, Hkv, T, W, kb, vb, seed=640 + Hq)
+    if Hq == 72:
+        q[:, 71] = 0          # the padding head: its output is ignored by a caller, here it is simply a zero query
+    st, want = rc.decode_attn(u16(q))
+    assert st == 0
+    got = run_attn(gc, shape, cfg, q, n_splits=n_splits)
+    assert_attn_close(got, want, f"Hq={Hq} Hkv={Hkv}", tight=True)
+    # fused step with the append inside, twice
+    kn, vn = synth.gen_layer_numpy(641, 1, B, Hkv, Hkv, 2)[1:]
+    qt = torch.from_numpy(q).cuda()
+    out = torch.zeros_like(qt)
+    ws = torch.zeros(kv.workspace_bytes(shape, gc.T_cap), dtype=torch.uint8, device="cuda")
+    for s in range(2):
+        assert rc.append(u16(kn[:, :, s]), u16(vn[:, :, s])) == 0
+        st, want = rc.decode_attn(u16(q))
+        kv.decode_step(shape, cfg, torch.from_numpy(kn[:, :, s].copy()).cuda(), torch.from_numpy(vn[:, :, s].copy()).cuda(), qt, gc, out, ws, n_splits=n_splits)
+        torch.cuda.synchronize()
+        assert_attn_close(t16(out), want, f"Hq={Hq} Hkv={Hkv} step {s}", tight=True)
+    assert not ws[: 4 * shape.units * max(1, Hq // Hkv // 8)].any()
+
+
 def test_decode_steps_with_window_length_zero():
     """Window length 0: every 32nd step the appended token is itself among the 32 that are quantized (it never
     passes through the ring); in between the window holds 1..31 tokens."""
@@ -282,6 +311,9 @@ def test_attn_error_returns():
     assert e.value.status == -6
     with pytest.raises(kv.KVMixError) as e:      # G = 3 unsupported
         kv.decode_attn(kv.Shape(1, 6, 2), cfg, qt, gc, out, None)
+    assert e.value.status == -4
+    with pytest.raises(kv.KVMixError) as e:      # G = 12: above 8 only multiples of 8
+        kv.decode_attn(kv.Shape(1, 24, 2), cfg, qt, gc, out, None)
     assert e.value.status == -4
     assert not out.any()
 
