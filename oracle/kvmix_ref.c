@@ -15,7 +15,10 @@
  *   - decode attention by its plain definition: softmax(scale * q K~^T) V~ in fp64, where
  *     K~, V~ are the dequantized packed tokens (x = q*s + min, Sec. 3.2.2 step 4) followed by
  *     the fp16 recent window (Sec. 3.3). The fused kernel of Sec. 3.4 item 2 reaches exactly
- *     this result; the fusion introduces no approximation.
+ *     this result; the fusion introduces no approximation;
+ *   - the Recent Pivotal Context count num_RPC = floor(r * current_RPC) of Sec. 3.3 and the ageing it drives, with
+ *     separate counts for Keys and Values (the ratios of Sec. 4.2: 20 % at 3/4 bit, 10 % at 2 bit): Keys leave
+ *     the fp16 window in whole groups of 32 tokens, Values token by token.
  *
  * Readings of the paper where it is silent (each one is listed in the design document):
  *   round = round-half-to-even; scale and minimum are stored as fp16 and the quantizer uses the
@@ -26,7 +29,9 @@
  *
  * Pins (tests/test_oracle_*.py): brute-force nearest-level search, closed-form groups, the
  * round-trip bound |x - x~| <= s_i/2, bijectivity of the packing, reduction to library
- * attention when nothing is quantized, invariances of softmax attention.
+ * attention when nothing is quantized, invariances of softmax attention; for the ageing: the window-count
+ * sequences the formula gives for r = 0.2 and 0.1, records identical to those of the one-pass quantizer whatever
+ * the order in which tokens left, attention equal to library attention over the per-token mix of sources.
  * Parity unpinned: the physical bit order, the tie rule, the fp16 storage of scale/minimum and
  * the 3-bit step reading are readings, the paper prints no worked numeric example.
  */
@@ -50,7 +55,10 @@ typedef struct {
   uint32_t* packed;  /* tile records, see record_of() */
   uint16_t* k_win;   uint16_t* v_win;
   int32_t T_cap, W_cap, n_q, n_w, w0;
+  int32_t v_lead;    /* packed Value tokens minus packed Key tokens (Sec. 3.3: the two ratios of a layer may differ) */
 } ref_layer_cache; /* all pointers are host memory */
+/* The sequence has n = n_q + n_w tokens. Keys of tokens [0, n_q) are packed, Values of tokens [0, n_q + v_lead);
+ * every later Key / Value is an fp16 row of k_win / v_win, token t in ring slot (w0 + t - n_q) mod W_cap. */
 
 /* ------------------------------------------------------------------ fp16 <-> binary64 */
 
@@ -205,6 +213,17 @@ static void put_code(uint32_t* tile, int bits, code_pos p, int code) {
   }
 }
 
+/* overwrite instead of OR: for a token whose neighbours in the same words are already in place */
+static void set_code(uint32_t* tile, int bits, code_pos p, int code) {
+  if (bits == 3) {
+    tile[p.word] &= ~(3u << p.bit);
+    tile[p.hword] &= ~(1u << p.hbit);
+  } else {
+    tile[p.word] &= ~((uint32_t)qmax_of(bits) << p.bit);
+  }
+  put_code(tile, bits, p, code);
+}
+
 static int get_code(const uint32_t* tile, int bits, code_pos p) {
   if (bits == 3) return (int)((tile[p.word] >> p.bit) & 3u) + 4 * (int)((tile[p.hword] >> p.hbit) & 1u);
   return (int)((tile[p.word] >> p.bit) & (uint32_t)qmax_of(bits));
@@ -339,14 +358,24 @@ int kvmix_ref_quantize_pack(const ref_shape* sh, const ref_layer_cfg* cfg, const
                                token_stride, 1, batch_stride, head_stride, n_tokens, t0, c);
 }
 
+/* ring slot of token t (both windows) */
+static int slot_of(const ref_layer_cache* c, int t) {
+  int W = c->W_cap, s = (c->w0 + t - c->n_q) % W;
+  return s < 0 ? s + W : s;
+}
+/* tokens that live in the ring: from the older of the two packed fronts to the newest */
+static int ring_tokens(const ref_layer_cache* c) { return c->n_w + (c->v_lead < 0 ? -c->v_lead : 0); }
+
 /* Append one token per unit to the window ring; flush the oldest 32 into the packed cache when
- * the window holds window + 32 tokens (Sec. 3.3: older tokens are quantized, recent ones stay). */
+ * the window holds window + 32 tokens (Sec. 3.3: older tokens are quantized, recent ones stay).
+ * window == -1: nothing is flushed here, ageing is left to kvmix_ref_flush. */
 int kvmix_ref_append(const ref_shape* sh, const ref_layer_cfg* cfg, const uint16_t* k_new, const uint16_t* v_new,
                      ref_layer_cache* c) {
   int st = check_common(sh, cfg);
   if (st) return st;
   if (!k_new || !v_new || !c) return REF_ERR_NULL;
-  if (c->n_w >= c->W_cap) return REF_ERR_BAD_SHAPE;
+  if (ring_tokens(c) >= c->W_cap) return REF_ERR_BAD_SHAPE;
+  if (cfg->window >= 0 && c->v_lead != 0) return REF_ERR_BAD_SHAPE;
   int units = sh->B * sh->Hkv, W = c->W_cap;
   int slot = (c->w0 + c->n_w) % W;
   for (int u = 0; u < units; u++)
@@ -355,7 +384,7 @@ int kvmix_ref_append(const ref_shape* sh, const ref_layer_cfg* cfg, const uint16
       c->v_win[((size_t)u * W + slot) * D_HEAD + d] = v_new[(size_t)u * D_HEAD + d];
     }
   c->n_w += 1;
-  if (cfg->k_bits != 16 && c->n_w == cfg->window + TILE_TOKENS) {
+  if (cfg->k_bits != 16 && cfg->window >= 0 && c->n_w == cfg->window + TILE_TOKENS) {
     if (c->n_q + TILE_TOKENS > c->T_cap) return REF_ERR_BAD_SHAPE;
     /* the oldest 32 tokens are slots w0 .. w0+31 (w0 and W_cap are multiples of 32) */
     st = quantize_pack_strided(sh, cfg, c->k_win + (size_t)c->w0 * D_HEAD, c->v_win + (size_t)c->w0 * D_HEAD,
@@ -370,31 +399,86 @@ int kvmix_ref_append(const ref_shape* sh, const ref_layer_cfg* cfg, const uint16
   return REF_OK;
 }
 
-/* Dequantized packed tokens of one unit as binary64: out[t*128 + d], t < n_q. */
-static void dequant_unit(const ref_layer_cfg* cfg, int which, const ref_layer_cache* c, int u, double* out) {
+/* Dequantized packed token t of one unit as binary64: out[d] (which = 0 Key, 1 Value). */
+static void dequant_token(const ref_layer_cfg* cfg, int which, const ref_layer_cache* c, int u, int t, double* out) {
   int kb = cfg->k_bits, vb = cfg->v_bits, bits = which ? vb : kb;
-  uint8_t codes[TILE_TOKENS * D_HEAD];
-  for (int tt = 0; tt < c->n_q / TILE_TOKENS; tt++) {
-    uint32_t* rec = record_of(c, kb, vb, u, tt);
-    kvmix_ref_unpack_tile(which, bits, which ? value_codes_of(rec, kb) : key_codes_of(rec), codes);
-    for (int tau = 0; tau < TILE_TOKENS; tau++)
-      for (int d = 0; d < D_HEAD; d++) {
-        uint16_t s_h, z_h; int i;
-        if (which == 0) { s_h = key_meta_fetch(rec, d, 0); z_h = key_meta_fetch(rec, d, 1); i = tau; }   /* group along tokens */
-        else { s_h = value_meta_fetch(rec, tau, d / GROUP, 0); z_h = value_meta_fetch(rec, tau, d / GROUP, 1); i = d % GROUP; } /* along channels */
-        out[(size_t)(tt * TILE_TOKENS + tau) * D_HEAD + d] = kvmix_ref_dequant_elem(codes[tau * D_HEAD + d], i, bits, s_h, z_h);
-      }
+  int tau = t % TILE_TOKENS;
+  uint32_t* rec = record_of(c, kb, vb, u, t / TILE_TOKENS);
+  const uint32_t* words = which ? value_codes_of(rec, kb) : key_codes_of(rec);
+  for (int d = 0; d < D_HEAD; d++) {
+    uint16_t s_h, z_h; int i;
+    if (which == 0) { s_h = key_meta_fetch(rec, d, 0); z_h = key_meta_fetch(rec, d, 1); i = tau; }   /* group along tokens */
+    else { s_h = value_meta_fetch(rec, tau, d / GROUP, 0); z_h = value_meta_fetch(rec, tau, d / GROUP, 1); i = d % GROUP; } /* along channels */
+    int code = get_code(words, bits, which ? pos_value(bits, tau, d) : pos_key(bits, tau, d));
+    out[d] = kvmix_ref_dequant_elem(code, i, bits, s_h, z_h);
   }
 }
 
+/* out: [units][count][128] with count = n_q (Keys) or n_q + v_lead (Values). */
 int kvmix_ref_dequant(const ref_shape* sh, const ref_layer_cfg* cfg, const ref_layer_cache* c, int which, double* out) {
   int st = check_common(sh, cfg);
   if (st) return st;
   if (!c || !out) return REF_ERR_NULL;
   if (cfg->k_bits == 16) return c->n_q == 0 ? REF_OK : REF_ERR_BAD_BITS;
-  int units = sh->B * sh->Hkv;
+  int units = sh->B * sh->Hkv, count = c->n_q + (which ? c->v_lead : 0);
   for (int u = 0; u < units; u++)
-    dequant_unit(cfg, which, c, u, out + (size_t)u * c->n_q * D_HEAD);
+    for (int t = 0; t < count; t++)
+      dequant_token(cfg, which, c, u, t, out + ((size_t)u * count + t) * D_HEAD);
+  return REF_OK;
+}
+
+/* Sec. 3.3: num_RPC = floor(r * current_RPC), the product taken in binary64. */
+int kvmix_ref_rpc_next(double r, int current) { return (int)floor(r * (double)current); }
+
+/* Sec. 3.3, Fig. 4: the tokens that are no longer among the keep_k (Keys) / keep_v (Values) most recent ones are
+ * quantized and join the packed part; the kept ones stay fp16. Keys can only leave in whole groups of 32 tokens
+ * (Sec. 3.2.1: a Key group runs along the tokens), so the Key front moves to the largest multiple of 32 that
+ * leaves at least keep_k tokens; a Value group is one token's 32 channels, so Values leave token by token.
+ * Neither front moves back. */
+int kvmix_ref_flush(const ref_shape* sh, const ref_layer_cfg* cfg, ref_layer_cache* c, int keep_k, int keep_v) {
+  int st = check_common(sh, cfg);
+  if (st) return st;
+  if (!c) return REF_ERR_NULL;
+  if (cfg->k_bits == 16) return REF_ERR_BAD_BITS;
+  if (keep_k < 0 || keep_v < 0) return REF_ERR_BAD_SHAPE;
+  int n = c->n_q + c->n_w, n_qv = c->n_q + c->v_lead;
+  int nk = n - keep_k, nv = n - keep_v;
+  if (nk < 0) nk = 0;
+  nk -= nk % TILE_TOKENS;
+  if (nk < c->n_q) nk = c->n_q;
+  if (nv < n_qv) nv = n_qv;
+  if (nk > c->T_cap || nv > c->T_cap) return REF_ERR_BAD_SHAPE;
+  int units = sh->B * sh->Hkv, kb = cfg->k_bits, vb = cfg->v_bits, W = c->W_cap;
+  for (int u = 0; u < units; u++) {
+    uint16_t x[GROUP]; uint8_t gc[GROUP]; uint16_t s_h, z_h;
+    for (int t0 = c->n_q; t0 < nk; t0 += TILE_TOKENS) {          /* Key tiles */
+      uint32_t* rec = record_of(c, kb, vb, u, t0 / TILE_TOKENS);
+      uint8_t codes[TILE_TOKENS * D_HEAD];
+      for (int d = 0; d < D_HEAD; d++) {
+        for (int tau = 0; tau < TILE_TOKENS; tau++) x[tau] = c->k_win[((size_t)u * W + slot_of(c, t0 + tau)) * D_HEAD + d];
+        kvmix_ref_quantize_group(x, kb, gc, &s_h, &z_h);
+        key_meta_store(rec, d, 0, s_h);
+        key_meta_store(rec, d, 1, z_h);
+        for (int tau = 0; tau < TILE_TOKENS; tau++) codes[tau * D_HEAD + d] = gc[tau];
+      }
+      kvmix_ref_pack_tile(0, kb, codes, key_codes_of(rec));
+    }
+    for (int t = n_qv; t < nv; t++) {                            /* Value tokens */
+      uint32_t* rec = record_of(c, kb, vb, u, t / TILE_TOKENS);
+      int tau = t % TILE_TOKENS;
+      for (int g = 0; g < D_HEAD / GROUP; g++) {
+        for (int e = 0; e < GROUP; e++) x[e] = c->v_win[((size_t)u * W + slot_of(c, t)) * D_HEAD + g * GROUP + e];
+        kvmix_ref_quantize_group(x, vb, gc, &s_h, &z_h);
+        value_meta_store(rec, tau, g, 0, s_h);
+        value_meta_store(rec, tau, g, 1, z_h);
+        for (int e = 0; e < GROUP; e++) set_code(value_codes_of(rec, kb), vb, pos_value(vb, tau, g * GROUP + e), gc[e]);
+      }
+    }
+  }
+  c->w0 = slot_of(c, nk);
+  c->n_q = nk;
+  c->n_w = n - nk;
+  c->v_lead = nv - nk;
   return REF_OK;
 }
 
@@ -405,8 +489,9 @@ int kvmix_ref_decode_attn(const ref_shape* sh, const ref_layer_cfg* cfg, const u
   if (st) return st;
   if (!q || !c || !out) return REF_ERR_NULL;
   if (cfg->k_bits == 16 && c->n_q != 0) return REF_ERR_BAD_BITS;
-  if (c->n_q + c->n_w < 1 || c->n_q % TILE_TOKENS || c->n_w > c->W_cap) return REF_ERR_BAD_SHAPE;
-  int units = sh->B * sh->Hkv, G = sh->Hq / sh->Hkv, T = c->n_q + c->n_w, W = c->W_cap;
+  if (c->n_q + c->n_w < 1 || c->n_q % TILE_TOKENS || ring_tokens(c) > c->W_cap) return REF_ERR_BAD_SHAPE;
+  if (c->n_q + c->v_lead < 0 || c->v_lead > c->n_w) return REF_ERR_BAD_SHAPE;
+  int units = sh->B * sh->Hkv, G = sh->Hq / sh->Hkv, T = c->n_q + c->n_w, W = c->W_cap, n_qv = c->n_q + c->v_lead;
   double scale = softmax_scale > 0.0f ? (double)softmax_scale : 1.0 / sqrt((double)D_HEAD);
 #pragma omp parallel for schedule(dynamic, 1)
   for (int u = 0; u < units; u++) {
@@ -414,13 +499,12 @@ int kvmix_ref_decode_attn(const ref_shape* sh, const ref_layer_cfg* cfg, const u
     double* Kt = (double*)malloc(sizeof(double) * (size_t)T * D_HEAD);
     double* Vt = (double*)malloc(sizeof(double) * (size_t)T * D_HEAD);
     double* a = (double*)malloc(sizeof(double) * (size_t)T);
-    if (c->n_q) { dequant_unit(cfg, 0, c, u, Kt); dequant_unit(cfg, 1, c, u, Vt); }
-    for (int r = 0; r < c->n_w; r++) {                   /* window tokens, oldest first */
-      int slot = (c->w0 + r) % W;
-      for (int d = 0; d < D_HEAD; d++) {
-        Kt[(size_t)(c->n_q + r) * D_HEAD + d] = kvmix_ref_h2d(c->k_win[((size_t)u * W + slot) * D_HEAD + d]);
-        Vt[(size_t)(c->n_q + r) * D_HEAD + d] = kvmix_ref_h2d(c->v_win[((size_t)u * W + slot) * D_HEAD + d]);
-      }
+    for (int t = 0; t < T; t++) {                        /* packed tokens dequantized, window tokens as they are */
+      int slot = slot_of(c, t);
+      if (t < c->n_q) dequant_token(cfg, 0, c, u, t, Kt + (size_t)t * D_HEAD);
+      else for (int d = 0; d < D_HEAD; d++) Kt[(size_t)t * D_HEAD + d] = kvmix_ref_h2d(c->k_win[((size_t)u * W + slot) * D_HEAD + d]);
+      if (t < n_qv) dequant_token(cfg, 1, c, u, t, Vt + (size_t)t * D_HEAD);
+      else for (int d = 0; d < D_HEAD; d++) Vt[(size_t)t * D_HEAD + d] = kvmix_ref_h2d(c->v_win[((size_t)u * W + slot) * D_HEAD + d]);
     }
     for (int hg = 0; hg < G; hg++) {
       int h = j * G + hg;                                /* query head h reads kv head h / G */

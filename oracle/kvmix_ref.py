@@ -23,7 +23,7 @@ class _Cfg(C.Structure):
 
 class _Cache(C.Structure):
     _fields_ = [("packed", C.c_void_p), ("k_win", C.c_void_p), ("v_win", C.c_void_p)] + \
-               [(n, C.c_int32) for n in ("T_cap", "W_cap", "n_q", "n_w", "w0")]
+               [(n, C.c_int32) for n in ("T_cap", "W_cap", "n_q", "n_w", "w0", "v_lead")]
 
 
 def lib():
@@ -59,6 +59,10 @@ def lib():
         L.kvmix_ref_append.argtypes = [C.c_void_p] * 5
         L.kvmix_ref_dequant.restype = C.c_int
         L.kvmix_ref_dequant.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p]
+        L.kvmix_ref_rpc_next.restype = C.c_int
+        L.kvmix_ref_rpc_next.argtypes = [C.c_double, C.c_int]
+        L.kvmix_ref_flush.restype = C.c_int
+        L.kvmix_ref_flush.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int]
         L.kvmix_ref_decode_attn.restype = C.c_int
         L.kvmix_ref_decode_attn.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_float, C.c_void_p]
         _lib = L
@@ -139,6 +143,11 @@ def unpack_literal3(words):
     return codes
 
 
+def rpc_next(r: float, current: int) -> int:
+    """num_RPC = floor(r * current_RPC) (Sec. 3.3)."""
+    return lib().kvmix_ref_rpc_next(float(r), int(current))
+
+
 def record_words(k_bits: int, v_bits: int) -> int:
     return lib().kvmix_ref_record_words(int(k_bits), int(v_bits))
 
@@ -177,7 +186,7 @@ class RefCache:
         self.packed = np.zeros((self.units, tiles, record_words(kb, vb)), np.uint32)
         self.k_win = np.zeros((self.units, W_cap, 128), np.uint16)
         self.v_win = np.zeros((self.units, W_cap, 128), np.uint16)
-        self.c = _Cache(_ptr(self.packed).value, _ptr(self.k_win).value, _ptr(self.v_win).value, T_cap, W_cap, 0, 0, 0)
+        self.c = _Cache(_ptr(self.packed).value, _ptr(self.k_win).value, _ptr(self.v_win).value, T_cap, W_cap, 0, 0, 0, 0)
 
     def fields(self):
         """The record buffer cut into codes / scales / minima (copies), see split_records."""
@@ -194,6 +203,13 @@ class RefCache:
     n_q = property(lambda self: self.c.n_q)
     n_w = property(lambda self: self.c.n_w)
     w0 = property(lambda self: self.c.w0)
+    v_lead = property(lambda self: self.c.v_lead)
+    n_qv = property(lambda self: self.c.n_q + self.c.v_lead)       # packed Value tokens
+    n = property(lambda self: self.c.n_q + self.c.n_w)             # tokens of the sequence
+
+    def flush(self, keep_k, keep_v):
+        """Age the cache: at most the keep_k / keep_v most recent Keys / Values stay fp16 (Keys in steps of 32)."""
+        return lib().kvmix_ref_flush(C.byref(self.shape), C.byref(self.cfg), C.byref(self.c), int(keep_k), int(keep_v))
 
     def quantize_pack(self, k, v, t0=None):
         """k, v: uint16 [B][Hkv][n_tokens][128] contiguous. Appends at t0 (default n_q) and advances n_q."""
@@ -227,7 +243,7 @@ class RefCache:
         return lib().kvmix_ref_append(C.byref(self.shape), C.byref(self.cfg), _ptr(k_new), _ptr(v_new), C.byref(self.c))
 
     def dequant(self, which):
-        out = np.zeros((self.units, self.c.n_q, 128), np.float64)
+        out = np.zeros((self.units, self.c.n_q + (self.c.v_lead if which else 0), 128), np.float64)
         st = lib().kvmix_ref_dequant(C.byref(self.shape), C.byref(self.cfg), C.byref(self.c), int(which), _ptr(out))
         assert st == 0, st
         return out
