@@ -61,9 +61,18 @@
  *
  * Recent window (fp16, ring buffer of W_cap slots, W_cap % 32 == 0, W_cap >= window + 32)
  *   k_win, v_win : [units][W_cap][128]   (channel contiguous: appending a token writes one full row of each)
- *   The n_w valid tokens sit in slots (w0 + r) % W_cap, r = 0..n_w-1, oldest first;
- *   w0 % 32 == 0. Both windows must hold finite values in every slot (zero-fill at allocation):
- *   slots outside the n_w valid ones are masked by multiplying with zero, not skipped.
+ *   The sequence has n = n_q + n_w tokens; token t >= n_q sits in slot (w0 + t - n_q) % W_cap of both windows, so
+ *   the n_w window tokens are slots (w0 + r) % W_cap, r = 0..n_w-1, oldest first; w0 % 32 == 0. Both windows must
+ *   hold finite values in every slot (zero-fill at allocation): slots outside the valid ones are masked by
+ *   multiplying with zero, not skipped.
+ *   Keys and Values may age at fronts of their own (Sec. 3.3: the ratio of a layer's Keys and Values may differ):
+ *   Keys of tokens [0, n_q) are packed, Values of tokens [0, n_q + v_lead). A Key group runs along 32 tokens, so
+ *   the Key front n_q is a multiple of 32; a Value group is one token's 32 channels, so the Value front may stand
+ *   anywhere, also inside a tile (the tile's record then holds the Value codes and metadata of its first tokens
+ *   only, the rest of those fields is unspecified until their tokens arrive). With v_lead < 0 the Value rows of
+ *   tokens [n_q + v_lead, n_q) are still in v_win, in the slots the formula above gives (the ring then holds
+ *   n_w - v_lead tokens, which must fit W_cap). v_lead == 0, Keys and Values ageing together, is what every call
+ *   but kvmix_flush produces, and the only state the fixed-window calls (window >= 0) accept.
  *
  * Numeric preconditions (not checked on the device)
  *   - all K / V / q inputs are finite (Sec. 3.2.2 defines the quantizer on real numbers only);
@@ -133,7 +142,9 @@ typedef struct {
 typedef struct {
   int32_t k_bits; /* 1, 2, 3, 4, or 16 (= keep the whole layer in the fp16 window) */
   int32_t v_bits; /* same set; 16 only together with k_bits == 16 */
-  int32_t window; /* number of most recent tokens kept in fp16 (the RPC count), multiple of 32 */
+  int32_t window; /* number of most recent tokens kept in fp16 (the RPC count), multiple of 32: the appending calls
+                     flush 32 tokens whenever window + 32 are held. -1: the appending calls flush nothing, ageing is
+                     driven by kvmix_flush (Sec. 3.3's count, kvmix_rpc_next) */
 } kvmix_layer_cfg;
 
 /* One layer's cache: caller-owned device buffers, host-side counters. */
@@ -145,6 +156,7 @@ typedef struct {
   int32_t n_q;   /* packed tokens (multiple of 32), the oldest n_q tokens of the sequence */
   int32_t n_w;   /* valid window tokens */
   int32_t w0;    /* ring start slot (multiple of 32) */
+  int32_t v_lead; /* packed Value tokens minus packed Key tokens, 0 unless kvmix_flush moved the fronts apart */
 } kvmix_layer_cache;
 
 int kvmix_version(void);
@@ -158,8 +170,8 @@ int kvmix_cache_bytes(const kvmix_shape* shape, const kvmix_layer_cfg* cfg, int 
                       size_t* packed_b, size_t* win_b);
 
 /* Workspace needed by kvmix_decode_attn for any context up to T_max packed tokens (split
- * partials + arrival counters). The workspace must be zero-filled once before first use;
- * every call leaves the counters zero again. */
+ * partials + arrival counters, and the partial of the tokens between the two fronts when v_lead != 0). The
+ * workspace must be zero-filled once before first use; every call leaves the counters zero again. */
 int kvmix_workspace_bytes(const kvmix_shape* shape, int T_max, size_t* bytes);
 
 /* Part 1 (Sec. 3.2.2 steps 1-4, Sec. 3.4 item 1). Quantize n_tokens (multiple of 32) fp16
@@ -181,7 +193,7 @@ int kvmix_quantize_pack(const kvmix_shape* shape, const kvmix_layer_cfg* cfg,
  * window then holds window + 32 tokens, the oldest 32 are quantized exactly as in
  * kvmix_quantize_pack and written at token offset n_q of the packed cache (joining the new codes to the
  * historical cache is an offset write into the pre-allocated buffer). Updates n_q, n_w, w0 in *cache (host).
- * With k_bits == 16 nothing is ever flushed (W_cap must hold the whole sequence). */
+ * With k_bits == 16 or window == -1 nothing is ever flushed (the ring must have a free slot). */
 int kvmix_append(const kvmix_shape* shape, const kvmix_layer_cfg* cfg,
                  const uint16_t* k_new, const uint16_t* v_new,
                  kvmix_layer_cache* cache, void* stream);
@@ -192,7 +204,10 @@ int kvmix_append(const kvmix_shape* shape, const kvmix_layer_cfg* cfg,
  * where Kt, Vt are the dequantized packed tokens followed by the fp16 window tokens.
  * q, out: fp16 [B][Hq][128]. softmax_scale <= 0 selects 1/sqrt(D). Accumulation is fp32.
  * n_splits: number of context splits per unit (split-K), 0 = chosen by the library.
- * workspace: see kvmix_workspace_bytes (may be NULL when the effective n_splits is 1). */
+ * workspace: see kvmix_workspace_bytes (may be NULL when the effective n_splits is 1 and v_lead == 0).
+ * With v_lead != 0 the tokens from the tile of the older front up to the tile end of the younger one (each Key and
+ * each Value taken from where it lives: packed and dequantized, or fp16) are worked on by a launch of their own that
+ * goes first and leaves one more partial in the workspace, which the main launch's merge includes. */
 int kvmix_decode_attn(const kvmix_shape* shape, const kvmix_layer_cfg* cfg, const uint16_t* q,
                       const kvmix_layer_cache* cache, float softmax_scale, uint16_t* out,
                       void* workspace, size_t workspace_bytes, int n_splits, void* stream);
@@ -229,15 +244,30 @@ int kvmix_append_tokens(const kvmix_shape* shape, const kvmix_layer_cfg* cfg,
  * that row from k_new / v_new and stores it into the window (Sec. 3.4 item 1 in spirit: no separate pass over
  * the cache for the new token). On the step where the window overflows one quantize-and-pack launch over the 32
  * oldest window tokens goes first (with window == 0 the new token is one of them: append, pack, then a plain
- * attention launch). Updates n_q, n_w, w0 in *cache (host). k_new, v_new (16-byte aligned) must stay valid until
+ * attention launch). With window == -1 nothing is flushed; when v_lead != 0 and the new token shares its tile with
+ * the younger front, the append is a launch of its own. Updates n_q, n_w, w0 in *cache (host). k_new, v_new (16-byte aligned) must stay valid until
  * the launches have run. */
 int kvmix_decode_step(const kvmix_shape* shape, const kvmix_layer_cfg* cfg,
                       const uint16_t* k_new, const uint16_t* v_new, const uint16_t* q,
                       kvmix_layer_cache* cache, float softmax_scale, uint16_t* out,
                       void* workspace, size_t workspace_bytes, int n_splits, void* stream);
 
-/* Test helper: dequantize the n_q packed tokens back to fp32 (x = code*s_i + mn evaluated in
- * fp32), which = 0 for K, 1 for V; out is [units][n_q][128]. */
+/* Sec. 3.3: num_RPC = floor(r * current_RPC) for a layer's Keys (r_k, current_k) and Values (r_v, current_v), the
+ * products taken in binary64; current_RPC = new tokens of this step + RPCs kept so far. Host arithmetic only.
+ * Ratios outside [0, 1] or negative counts: KVMIX_ERR_BAD_SHAPE. (Sec. 4.2 uses r = 0.2 at 3/4 bit, 0.1 at 2 bit.) */
+int kvmix_rpc_next(double r_k, double r_v, int current_k, int current_v, int* num_k, int* num_v);
+
+/* Ageing by count (Sec. 3.3, Fig. 4): tokens that are no longer among the keep_k most recent lose their fp16 Key,
+ * those no longer among the keep_v most recent their fp16 Value; both are quantized as in kvmix_quantize_pack, from
+ * the ring, in one launch. Keys leave in whole groups of 32 tokens: the Key front moves to the largest multiple of
+ * 32 that is <= n - keep_k; Values leave token by token: the Value front moves to n - keep_v. Neither front moves
+ * back (a count larger than what is held changes nothing). Updates n_q, n_w, w0, v_lead in *cache (host).
+ * KVMIX_ERR_BAD_SHAPE when a front would pass T_cap, KVMIX_ERR_BAD_BITS for a 16-bit layer. */
+int kvmix_flush(const kvmix_shape* shape, const kvmix_layer_cfg* cfg, kvmix_layer_cache* cache,
+                int keep_k, int keep_v, void* stream);
+
+/* Test helper: dequantize the packed tokens back to fp32 (x = code*s_i + mn evaluated in fp32), which = 0 for K
+ * (n_q tokens), 1 for V (n_q + v_lead tokens); out is [units][that count][128]. */
 int kvmix_dequant(const kvmix_shape* shape, const kvmix_layer_cfg* cfg,
                   const kvmix_layer_cache* cache, int which, float* out, void* stream);
 

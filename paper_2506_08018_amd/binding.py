@@ -30,7 +30,7 @@ class LayerCfg(C.Structure):
 
 class _CacheStruct(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("packed", "k_win", "v_win")] + \
-               [(n, C.c_int32) for n in ("T_cap", "W_cap", "n_q", "n_w", "w0")]
+               [(n, C.c_int32) for n in ("T_cap", "W_cap", "n_q", "n_w", "w0", "v_lead")]
 
 
 def lib():
@@ -64,6 +64,10 @@ def lib():
         L.kvmix_decode_step.argtypes = [P, P, P, P, P, P, C.c_float, P, P, SZ, I, P]
         L.kvmix_stream_read.restype = I
         L.kvmix_stream_read.argtypes = [P, SZ, I, I, P, P]
+        L.kvmix_rpc_next.restype = I
+        L.kvmix_rpc_next.argtypes = [C.c_double, C.c_double, I, I, P, P]
+        L.kvmix_flush.restype = I
+        L.kvmix_flush.argtypes = [P, P, P, I, I, P]
         L.kvmix_dequant.restype = I
         L.kvmix_dequant.argtypes = [P, P, P, I, P, P]
         _lib = L
@@ -114,8 +118,11 @@ class LayerCache:
         z = lambda n: torch.zeros(max(n, 16), dtype=torch.uint8, device=device)
         self.packed = z(sz["packed"])
         self.k_win, self.v_win = z(sz["win"]), z(sz["win"])
-        self.c = _CacheStruct(self.packed.data_ptr(), self.k_win.data_ptr(), self.v_win.data_ptr(), T_cap, W_cap, 0, 0, 0)
+        self.c = _CacheStruct(self.packed.data_ptr(), self.k_win.data_ptr(), self.v_win.data_ptr(), T_cap, W_cap, 0, 0, 0, 0)
 
+    v_lead = property(lambda self: self.c.v_lead)
+    n_qv = property(lambda self: self.c.n_q + self.c.v_lead)
+    n = property(lambda self: self.c.n_q + self.c.n_w)
     n_q = property(lambda self: self.c.n_q)
     n_w = property(lambda self: self.c.n_w)
     w0 = property(lambda self: self.c.w0)
@@ -197,6 +204,18 @@ def decode_step(shape, cfg, k_new, v_new, q, cache, out, workspace=None, softmax
     return out
 
 
+def rpc_next(r_k, r_v, current_k, current_v):
+    """(num_k, num_v) = floor(r * current) for a layer's Keys and Values."""
+    nk, nv = C.c_int(0), C.c_int(0)
+    _check(lib().kvmix_rpc_next(float(r_k), float(r_v), int(current_k), int(current_v), C.byref(nk), C.byref(nv)), "kvmix_rpc_next")
+    return nk.value, nv.value
+
+
+def flush(shape, cfg, cache, keep_k, keep_v, stream=None):
+    """Quantize the Keys / Values that are no longer among the keep_k / keep_v most recent ones."""
+    _check(lib().kvmix_flush(C.byref(shape), C.byref(cfg), C.byref(cache.c), int(keep_k), int(keep_v), _stream(stream)), "kvmix_flush")
+
+
 def stream_read(buf, workgroups, threads=768, nbytes=None, sink=None, stream=None):
     """Load-only pass over the first nbytes (default: all) of the CUDA tensor `buf` in the attention kernel's launch shape."""
     n = buf.numel() * buf.element_size() if nbytes is None else int(nbytes)
@@ -205,6 +224,6 @@ def stream_read(buf, workgroups, threads=768, nbytes=None, sink=None, stream=Non
 
 
 def dequant(shape, cfg, cache, which, out):
-    """out: fp32 CUDA tensor [units][n_q][128]."""
+    """out: fp32 CUDA tensor [units][n_q (Keys) or n_q + v_lead (Values)][128]."""
     _check(lib().kvmix_dequant(C.byref(shape), C.byref(cfg), C.byref(cache.c), which, out.data_ptr(), _stream()), "kvmix_dequant")
     return out

@@ -16,6 +16,7 @@ SOURCES = {
     # tile claims are single-lane LDS atomics whose result is taken late; the wave-reduction rewrite of
     # uniform atomics would put a wait right behind them
     "kvmix_attn.hip": ["-mllvm", "-amdgpu-atomic-optimizer-strategy=None"],
+    "kvmix_mixed.hip": ["-ffp-contract=off"],
     "kvmix_api.hip": [],
 }
 

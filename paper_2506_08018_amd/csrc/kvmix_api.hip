@@ -46,15 +46,26 @@ int check_shape_cfg(const kvmix_shape* sh, const kvmix_layer_cfg* cfg) {
   } else if (kb < 1 || kb > 4 || vb < 1 || vb > 4) {
     return KVMIX_ERR_BAD_BITS;
   }
-  if (cfg->window < 0 || cfg->window % kTile) return KVMIX_ERR_BAD_SHAPE;
+  if (cfg->window != -1 && (cfg->window < 0 || cfg->window % kTile)) return KVMIX_ERR_BAD_SHAPE;
   return KVMIX_OK;
 }
+
+// ring slot of token t (both windows)
+int slot_of(const kvmix_layer_cache* c, long long t) {
+  long long s = (c->w0 + t - c->n_q) % c->W_cap;
+  return (int)(s < 0 ? s + c->W_cap : s);
+}
+// tokens that live in the ring: from the older of the two fronts to the newest
+int ring_tokens(const kvmix_layer_cache* c) { return c->n_w + (c->v_lead < 0 ? -c->v_lead : 0); }
 
 int check_cache(const kvmix_layer_cfg* cfg, const kvmix_layer_cache* c, bool need_packed) {
   if (!c) return KVMIX_ERR_NULL;
   if (c->T_cap < 0 || c->T_cap % kTile || c->W_cap < kTile || c->W_cap % kTile) return KVMIX_ERR_BAD_SHAPE;
   if (c->n_q < 0 || c->n_q % kTile || c->n_q > c->T_cap) return KVMIX_ERR_BAD_SHAPE;
   if (c->n_w < 0 || c->n_w > c->W_cap || c->w0 < 0 || c->w0 >= c->W_cap || c->w0 % kTile) return KVMIX_ERR_BAD_SHAPE;
+  if (c->v_lead > c->n_w || (long long)c->n_q + c->v_lead < 0 || (long long)c->n_w - c->v_lead > c->W_cap || (long long)c->n_q + c->v_lead > c->T_cap)
+    return KVMIX_ERR_BAD_SHAPE;
+  if (c->v_lead != 0 && cfg->k_bits == 16) return KVMIX_ERR_BAD_BITS;
   if (!c->k_win || !c->v_win) return KVMIX_ERR_NULL;
   if (!aligned16(c->k_win) || !aligned16(c->v_win)) return KVMIX_ERR_ALIGN;
   if (cfg->k_bits == 16) return c->n_q == 0 ? KVMIX_OK : KVMIX_ERR_BAD_BITS;
@@ -129,7 +140,7 @@ int kvmix_workspace_bytes(const kvmix_shape* sh, int T_max, size_t* bytes) {
   if (!bytes) return KVMIX_ERR_NULL;
   if (T_max < 0) return KVMIX_ERR_BAD_SHAPE;
   const size_t units = (size_t)sh->B * sh->Hkv, G = (size_t)(sh->Hq / sh->Hkv);
-  *bytes = counters_bytes(out_units(sh)) + units * (size_t)max_splits(sh) * G * (kD + 2) * sizeof(float);
+  *bytes = counters_bytes(out_units(sh)) + units * (size_t)(max_splits(sh) + 1) * G * (kD + 2) * sizeof(float);
   return KVMIX_OK;
 }
 
@@ -169,13 +180,15 @@ int kvmix_append_tokens(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const
   if (n_tokens < 0) return KVMIX_ERR_BAD_SHAPE;
   if (token_stride < kD || head_stride < 0 || batch_stride < 0) return KVMIX_ERR_ALIGN;
   if (packed && (!aligned16(k_new) || !aligned16(v_new) || token_stride % 8 || head_stride % 8 || batch_stride % 8)) return KVMIX_ERR_ALIGN;
-  if (packed && c->W_cap < cfg->window + kTile) return KVMIX_ERR_BAD_SHAPE;
+  const bool ageing = packed && cfg->window >= 0;    // this call flushes; otherwise it only fills the ring
+  if (ageing && c->v_lead != 0) return KVMIX_ERR_BAD_SHAPE;
+  if (ageing && c->W_cap < cfg->window + kTile) return KVMIX_ERR_BAD_SHAPE;
   // dry run of the counters: nothing is launched unless everything fits
   {
     long long n_q = c->n_q, n_w = c->n_w;
-    if (n_w >= c->W_cap && n_tokens > 0) return KVMIX_ERR_BAD_SHAPE;
-    if (!packed) {
-      if (n_w + n_tokens > c->W_cap) return KVMIX_ERR_BAD_SHAPE;
+    if (ring_tokens(c) >= c->W_cap && n_tokens > 0) return KVMIX_ERR_BAD_SHAPE;
+    if (!ageing) {
+      if ((long long)ring_tokens(c) + n_tokens > c->W_cap) return KVMIX_ERR_BAD_SHAPE;
     } else {
       if (n_w >= cfg->window + kTile && n_tokens > 0) return KVMIX_ERR_BAD_SHAPE;   // a flush is overdue: not a state this library leaves
       const long long flushes = (n_w + n_tokens) >= cfg->window + kTile ? (n_w + n_tokens - cfg->window) / kTile : 0;
@@ -190,7 +203,7 @@ int kvmix_append_tokens(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const
   // of the surviving new rows into their ring slots (in this order: a new row may land in the slot of an old one
   // that the quantizer still has to read).
   const long long m = (long long)c->n_w + n_tokens;
-  const int F = packed && m >= cfg->window + kTile ? (int)((m - cfg->window) / kTile) : 0;
+  const int F = ageing && m >= cfg->window + kTile ? (int)((m - cfg->window) / kTile) : 0;
   if (F > 0) {
     QuantArgs a{};
     a.k = k_new; a.v = v_new;
@@ -231,10 +244,34 @@ int kvmix_append(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const uint16
 namespace {
 
 // Everything an attention launch needs, filled by plan_attention after all host-side checks have passed.
-struct AttnPlan { AttnArgs a; int kb, vb, G, units; };
+// `mixed`: the fronts of Keys and Values differ; the tokens between them go to a launch of their own (m) that
+// leaves one more partial for the main launch's merge.
+struct AttnPlan { AttnArgs a; int kb, vb, G, units; bool mixed; MixedArgs m; };
 
-size_t split_workspace_bytes(int units, int n_splits, int G) {
-  return counters_bytes(units * (G > 8 ? G / 8 : 1)) + (size_t)units * n_splits * G * (kD + 2) * sizeof(float);
+size_t split_workspace_bytes(int units, int n_parts, int G) {
+  return counters_bytes(units * (G > 8 ? G / 8 : 1)) + (size_t)units * n_parts * G * (kD + 2) * sizeof(float);
+}
+
+// How an attention call divides the n = n_q + n_w tokens of a cache whose Value front is n_q + v_lead:
+// tiles [0, packed_tiles) have Keys and Values packed, tokens [32 packed_tiles, t_a) are the mixed range, tokens
+// [t_a, n) are window tokens of both (t_a is a multiple of 32 unless it equals n).
+struct Fronts { int packed_tiles; long long t_a; int n_w_eff, w0_eff; bool mixed; };
+Fronts fronts_of(const kvmix_layer_cache* c, int n_w) {
+  Fronts f;
+  const long long n = (long long)c->n_q + n_w, n_qv = (long long)c->n_q + c->v_lead;
+  if (c->v_lead == 0) {
+    f.packed_tiles = c->n_q / kTile; f.t_a = c->n_q; f.n_w_eff = n_w; f.w0_eff = c->w0; f.mixed = false;
+    return f;
+  }
+  const long long lo = n_qv < c->n_q ? n_qv : c->n_q, hi = n_qv < c->n_q ? c->n_q : n_qv;
+  f.packed_tiles = (int)(lo / kTile);
+  long long t_a = (hi + kTile - 1) / kTile * kTile;
+  if (t_a > n) t_a = n;
+  f.t_a = t_a;
+  f.n_w_eff = (int)(n - t_a);
+  f.w0_eff = f.n_w_eff > 0 ? slot_of(c, t_a) : 0;
+  f.mixed = true;
+  return f;
 }
 
 // Validates an attention call against the cache state `c` (window count n_w) and fills the launch descriptor;
@@ -249,9 +286,10 @@ int plan_attention(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const uint
   if (!aligned16(q) || !aligned16(out)) return KVMIX_ERR_ALIGN;
   st = check_cache(cfg, c, false);
   if (st) return st;
-  if (c->n_q + n_w < 1 || n_w < 0 || n_w > c->W_cap) return KVMIX_ERR_BAD_SHAPE;
+  if (c->n_q + n_w < 1 || n_w < 0 || n_w > c->W_cap || (long long)n_w - (c->v_lead < 0 ? c->v_lead : 0) > c->W_cap) return KVMIX_ERR_BAD_SHAPE;
   const int units = sh->B * sh->Hkv, G = sh->Hq / sh->Hkv;
-  const int n_items = c->W_cap / kTile + c->n_q / kTile;
+  const Fronts fr = fronts_of(c, n_w);
+  const int n_items = c->W_cap / kTile + fr.packed_tiles;
   if (n_splits < 0 || n_splits > max_splits(sh)) return KVMIX_ERR_BAD_SHAPE;
   if (n_splits == 0) {
     // one workgroup occupies a whole compute unit (LDS): aim at one workgroup per unit, at least 8 tiles each
@@ -264,10 +302,11 @@ int plan_attention(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const uint
   }
   if (n_splits > n_items) n_splits = n_items;
   AttnArgs a{};
-  if (n_splits > 1) {
+  const int n_parts = n_splits + (fr.mixed ? 1 : 0);
+  if (n_parts > 1) {
     if (!workspace) return KVMIX_ERR_NULL;
     if (!aligned16(workspace)) return KVMIX_ERR_ALIGN;
-    if (workspace_bytes < split_workspace_bytes(units, n_splits, G)) return KVMIX_ERR_WORKSPACE;
+    if (workspace_bytes < split_workspace_bytes(units, n_parts, G)) return KVMIX_ERR_WORKSPACE;
     a.counters = reinterpret_cast<uint32_t*>(workspace);
     a.part = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) + counters_bytes(out_units(sh)));
   }
@@ -275,8 +314,8 @@ int plan_attention(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const uint
   a.packed = c->packed;
   a.k_win = c->k_win; a.v_win = c->v_win;
   a.k_new = k_new; a.v_new = v_new; a.k_win_w = c->k_win; a.v_win_w = c->v_win; a.new_slot = new_slot;
-  a.tiles_cap = c->T_cap / kTile; a.W_cap = c->W_cap; a.n_tiles = c->n_q / kTile; a.n_w = n_w; a.w0 = c->w0;
-  a.Hq = sh->Hq; a.Hkv = sh->Hkv; a.n_splits = n_splits;
+  a.tiles_cap = c->T_cap / kTile; a.W_cap = c->W_cap; a.n_tiles = fr.packed_tiles; a.n_w = fr.n_w_eff; a.w0 = fr.w0_eff;
+  a.Hq = sh->Hq; a.Hkv = sh->Hkv; a.n_splits = n_splits; a.n_parts = n_parts;
   a.items_q = n_items / n_splits; a.items_r = n_items % n_splits;
   const float scale = softmax_scale > 0.0f ? softmax_scale : 1.0f / std::sqrt((float)kD);
   a.scale_log2 = scale * 1.4426950408889634f;
@@ -284,10 +323,29 @@ int plan_attention(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const uint
   plan->kb = cfg->k_bits == 16 ? 2 : cfg->k_bits;
   plan->vb = cfg->v_bits == 16 ? 2 : cfg->v_bits;
   plan->G = G; plan->units = units;
+  plan->mixed = fr.mixed;
+  if (fr.mixed) {
+    // with the append inside the launch the new token must be a window token of the main launch
+    if (new_slot >= 0 && fr.n_w_eff < 1) return KVMIX_ERR_BAD_SHAPE;
+    MixedArgs m{};
+    m.q = q; m.packed = c->packed; m.k_win = c->k_win; m.v_win = c->v_win;
+    m.part = a.part; m.n_parts = n_parts; m.part_index = n_splits;
+    m.tiles_cap = a.tiles_cap; m.W_cap = c->W_cap; m.k_bits = plan->kb; m.v_bits = plan->vb;
+    m.n_qk = c->n_q; m.n_qv = c->n_q + c->v_lead;
+    m.t_begin = fr.packed_tiles * kTile; m.t_end = (int)fr.t_a;
+    m.slot_begin = slot_of(c, m.t_begin);
+    m.G = G > 8 ? 8 : G;
+    m.scale_log2 = a.scale_log2;
+    plan->m = m;
+  }
   return KVMIX_OK;
 }
 
 int launch_plan(const AttnPlan& p, void* stream) {
+  if (p.mixed) {
+    const hipError_t e = launch_mixed_fronts(p.m, p.units, p.G > 8 ? p.G / 8 : 1, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(e);
+  }
   const hipError_t e = launch_decode_attn(p.a, p.kb, p.vb, p.G, p.units, (hipStream_t)stream);
   return e == hipSuccess ? KVMIX_OK : hip_fail(e);
 }
@@ -357,13 +415,14 @@ int kvmix_decode_attn_static(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, 
   // every other check; the size that split count needs is then held against the array's fixed size.
   int st = plan_attention(sh, cfg, q, c, c->n_w, nullptr, nullptr, -1, softmax_scale, out, reinterpret_cast<void*>(256), ~(size_t)0, n_splits, &plan);
   if (st) return st;
-  if (plan.a.n_splits > 1) {
-    if (split_workspace_bytes(plan.units, plan.a.n_splits, plan.G) > kScratchBytes) return KVMIX_ERR_WORKSPACE;
+  if (plan.a.n_parts > 1) {
+    if (split_workspace_bytes(plan.units, plan.a.n_parts, plan.G) > kScratchBytes) return KVMIX_ERR_WORKSPACE;
     void* ptr = nullptr;
     st = scratch_address(&ptr, (hipStream_t)stream);
     if (st) return st;
     plan.a.counters = reinterpret_cast<uint32_t*>(ptr);
     plan.a.part = reinterpret_cast<float*>(reinterpret_cast<char*>(ptr) + counters_bytes(plan.units * (plan.G > 8 ? plan.G / 8 : 1)));
+    plan.m.part = plan.a.part;
   } else {
     plan.a.counters = nullptr; plan.a.part = nullptr;
   }
@@ -377,7 +436,8 @@ int kvmix_decode_step(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const u
   if (st) return st;
   if (!k_new || !v_new || !c) return KVMIX_ERR_NULL;
   AttnPlan plan;
-  const bool flush = cfg->k_bits != 16 && c->n_w + 1 == cfg->window + kTile;
+  const bool flush = cfg->k_bits != 16 && cfg->window >= 0 && c->n_w + 1 == cfg->window + kTile;
+  if (cfg->k_bits != 16 && cfg->window >= 0 && c->v_lead != 0) return KVMIX_ERR_BAD_SHAPE;   // fixed-window ageing needs one front
   if (flush) {
     // The 32 oldest window tokens move to the packed part before the attention reads them. Every check is made
     // first, the attention's against the counters as the flush will leave them, so that a failing call launches
@@ -417,9 +477,21 @@ int kvmix_decode_step(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const u
   }
   st = check_cache(cfg, c, cfg->k_bits != 16);
   if (st) return st;
-  if (c->n_w >= c->W_cap) return KVMIX_ERR_BAD_SHAPE;
+  if (ring_tokens(c) >= c->W_cap) return KVMIX_ERR_BAD_SHAPE;
   if (cfg->k_bits != 16 && c->W_cap < cfg->window + kTile) return KVMIX_ERR_BAD_SHAPE;
   if (!aligned16(k_new) || !aligned16(v_new)) return KVMIX_ERR_ALIGN;
+  if (c->v_lead != 0 && fronts_of(c, c->n_w + 1).t_a > (long long)c->n_q + c->n_w) {
+    // The new token shares its tile with the younger front: it belongs to the range between the fronts, which is
+    // read from the ring by a launch of its own. Plan against the counters as the append will leave them, append,
+    // then the two attention launches.
+    kvmix_layer_cache after = *c;
+    after.n_w += 1;
+    st = plan_attention(sh, cfg, q, &after, after.n_w, nullptr, nullptr, -1, softmax_scale, out, workspace, workspace_bytes, n_splits, &plan);
+    if (st) return st;
+    st = kvmix_append(sh, cfg, k_new, v_new, c, stream);
+    if (st) return st;
+    return launch_plan(plan, stream);
+  }
   const int slot = (c->w0 + c->n_w) % c->W_cap;
   // the kernel's window count includes the new token: it is read from k_new / v_new in place of its ring row (and stored)
   st = plan_attention(sh, cfg, q, c, c->n_w + 1, k_new, v_new, slot, softmax_scale, out, workspace, workspace_bytes, n_splits, &plan);
@@ -427,6 +499,53 @@ int kvmix_decode_step(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const u
   st = launch_plan(plan, stream);
   if (st) return st;
   c->n_w += 1;
+  return KVMIX_OK;
+}
+
+int kvmix_rpc_next(double r_k, double r_v, int current_k, int current_v, int* num_k, int* num_v) {
+  if (!num_k || !num_v) return KVMIX_ERR_NULL;
+  if (!(r_k >= 0.0 && r_k <= 1.0) || !(r_v >= 0.0 && r_v <= 1.0) || current_k < 0 || current_v < 0) return KVMIX_ERR_BAD_SHAPE;
+  *num_k = (int)std::floor(r_k * (double)current_k);
+  *num_v = (int)std::floor(r_v * (double)current_v);
+  return KVMIX_OK;
+}
+
+int kvmix_flush(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, kvmix_layer_cache* c, int keep_k, int keep_v, void* stream) {
+  int st = check_shape_cfg(sh, cfg);
+  if (st) return st;
+  if (cfg->k_bits == 16) return KVMIX_ERR_BAD_BITS;
+  st = check_cache(cfg, c, true);
+  if (st) return st;
+  if (keep_k < 0 || keep_v < 0) return KVMIX_ERR_BAD_SHAPE;
+  const long long n = (long long)c->n_q + c->n_w, n_qv = (long long)c->n_q + c->v_lead;
+  long long nk = n - keep_k, nv = n - keep_v;
+  if (nk < 0) nk = 0;
+  nk -= nk % kTile;
+  if (nk < c->n_q) nk = c->n_q;
+  if (nv < n_qv) nv = n_qv;
+  if (nk > c->T_cap || nv > c->T_cap) return KVMIX_ERR_BAD_SHAPE;
+  const bool k_moves = nk > c->n_q, v_moves = nv > n_qv;
+  if (!k_moves && !v_moves) return KVMIX_OK;
+  // one launch over the tiles that either side touches
+  long long first = k_moves ? c->n_q / kTile : n_qv / kTile, last = k_moves ? nk / kTile : (nv + kTile - 1) / kTile;
+  if (v_moves) {
+    if (n_qv / kTile < first) first = n_qv / kTile;
+    if ((nv + kTile - 1) / kTile > last) last = (nv + kTile - 1) / kTile;
+  }
+  QuantArgs a{};
+  a.k_ring = c->k_win; a.v_ring = c->v_win; a.W_cap = c->W_cap;
+  a.ring_w0 = slot_of(c, first * kTile);
+  fill_quant_dst(a, c);
+  a.tile0 = (int)first;
+  a.Hkv = sh->Hkv;
+  a.k_tile_a = c->n_q / kTile; a.k_tile_b = (int)(nk / kTile);
+  a.v_tok_a = (int)n_qv; a.v_tok_b = (int)nv;
+  const hipError_t e = launch_quantize_fronts(a, cfg->k_bits, cfg->v_bits, (int)(last - first), sh->B * sh->Hkv, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e);
+  c->w0 = slot_of(c, nk);
+  c->n_q = (int)nk;
+  c->n_w = (int)(n - nk);
+  c->v_lead = (int)(nv - nk);
   return KVMIX_OK;
 }
 
@@ -448,7 +567,7 @@ int kvmix_dequant(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const kvmix
   if (st) return st;
   DequantArgs a{};
   a.packed = c->packed;
-  a.out = out; a.tiles_cap = c->T_cap / kTile; a.n_tiles = c->n_q / kTile;
+  a.out = out; a.tiles_cap = c->T_cap / kTile; a.n_tokens = c->n_q + (which ? c->v_lead : 0);
   a.k_bits = cfg->k_bits; a.v_bits = cfg->v_bits; a.which = which;
   const hipError_t e = launch_dequant(a, sh->B * sh->Hkv, (hipStream_t)stream);
   return e == hipSuccess ? KVMIX_OK : hip_fail(e);

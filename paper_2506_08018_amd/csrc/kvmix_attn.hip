@@ -894,7 +894,7 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
   };
   uint16_t* outp = a.out + (size_t)uo * (G * kD);
 
-  if (a.n_splits == 1) {
+  if (a.n_parts == 1) {
     if constexpr (G <= 2) {
       // No barrier: a wave delivers its result and leaves; the last one to deliver combines them.
       // (LDS serves a wave's operations in order, so its results are in place before its count.)
@@ -945,12 +945,13 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
     combine(idx, M, Lsum, O);
     // agent-scope stores: written through to the level all XCDs share (no cache-wide flush needed)
     const int hh = idx / kD, d = idx % kD;
-    float* pp = a.part + (((size_t)uo * a.n_splits + sp) * G + hh) * (kD + 2);
+    float* pp = a.part + (((size_t)uo * a.n_parts + sp) * G + hh) * (kD + 2);
     if (d == 0) { st_agent(pp, M); st_agent(pp + 1, Lsum); }
     st_agent(pp + 2 + d, O);
   }
 
-  // ---- split merge: the last workgroup of the unit to arrive combines all partials
+  // ---- split merge: the last workgroup of the unit to arrive combines all partials (n_parts of them: one per
+  // split, and the one an earlier launch may have left for the tokens between a Key front and a Value front)
   // The partials were stored and are later loaded with agent scope, which the hardware keeps coherent
   // per access across the XCDs' L2s: waiting for the stores to complete is all the release needs.
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's partial stores have completed ...
@@ -963,16 +964,16 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
   if (!s_done) return;
   for (int idx = tid; idx < G * kD; idx += kThreads) {
     const int hh = idx / kD, d = idx % kD;
-    const float* base = a.part + ((size_t)uo * a.n_splits * G + hh) * (kD + 2);
+    const float* base = a.part + ((size_t)uo * a.n_parts * G + hh) * (kD + 2);
     const size_t stride = (size_t)G * (kD + 2);
     // one pass, kMergeBatch splits per round trip: the loads of a batch are issued together
     float M = -INFINITY, Lsum = 0.0f, O = 0.0f;
-    for (int s0 = 0; s0 < a.n_splits; s0 += kMergeBatch) {
+    for (int s0 = 0; s0 < a.n_parts; s0 += kMergeBatch) {
       float ms[kMergeBatch], ls[kMergeBatch], os[kMergeBatch];
 #pragma unroll
       for (int k = 0; k < kMergeBatch; k++) {
         ms[k] = -INFINITY; ls[k] = 0.0f; os[k] = 0.0f;
-        if (s0 + k < a.n_splits) {          // wave-uniform: no request for splits that do not exist
+        if (s0 + k < a.n_parts) {           // wave-uniform: no request for partials that do not exist
           const float* pp = base + (size_t)(s0 + k) * stride;
           ms[k] = ld_agent(pp);
           ls[k] = ld_agent(pp + 1);

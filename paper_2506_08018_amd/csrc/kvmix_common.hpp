@@ -63,6 +63,32 @@ __host__ __device__ inline void value_td(int l, int j, int hh, int slot, int& ta
   tau = 8 * kq + 2 * j + hh;
 }
 
+// x = code * s_i + min (Sec. 3.2.2 step 4) of token tau, channel d of a tile record, in fp32 (multiply, then add);
+// which = 0 Key, 1 Value. The straightforward form, for the helper kernels that are not bound by it.
+__device__ inline float dequant_elem(const uint32_t* rec, int k_bits, int v_bits, int which, int tau, int d) {
+  const uint16_t* meta = reinterpret_cast<const uint16_t*>(rec);
+  const int bits = which ? v_bits : k_bits;
+  const uint32_t* words = rec + kMetaWords + (which ? tile_words(k_bits) : 0);
+  int l, j, hh, slot, gi, ms, mz;
+  if (which == 0) {
+    const int ks = d / 32, kq = (d % 32) / 8, m = (tau % 8) / 4, i = 4 * (tau / 8) + tau % 4;
+    l = 16 * kq + i; j = (d % 8) / 2; hh = d % 2; slot = ks + 4 * m;
+    ms = key_meta_half(d, 0); mz = key_meta_half(d, 1); gi = tau;
+  } else {
+    l = 16 * (tau / 8) + d % 16; j = (tau % 8) / 2; hh = tau % 2; slot = d / 16;
+    ms = value_meta_half(tau, d / 32, 0); mz = value_meta_half(tau, d / 32, 1); gi = d % 32;
+  }
+  const CodePos p = pos_from_slots(bits, l, j, hh, slot);
+  int code;
+  if (bits == 3) code = ((words[p.word] >> p.bit) & 3u) + 4 * ((words[p.hword] >> p.hbit) & 1u);
+  else code = (words[p.word] >> p.bit) & ((1u << bits) - 1u);
+  const float s = (float)__builtin_bit_cast(half_t, meta[ms]);
+  const float mn = (float)__builtin_bit_cast(half_t, meta[mz]);
+  const float si = (bits == 3 && (gi == 10 || gi == 21)) ? (s * 7.0f) / 3.0f : s;
+  const float prod = (float)code * si;
+  return prod + mn;
+}
+
 // Launch descriptors filled by the C-ABI layer (host) and passed by value.
 struct QuantArgs {
   // The token sequence that is quantized: its rows [0, n_ring) are the ring slots (ring_w0 + r) % W_cap of the two
@@ -77,11 +103,15 @@ struct QuantArgs {
   int tiles_cap;   // tiles per unit in the packed cache
   int tile0;       // first destination tile
   int Hkv;
+  // Ageing with separate fronts (every row comes from the ring, row r of the launch is token 32*tile0 + r): the Key
+  // side is written for the destination tiles [k_tile_a, k_tile_b) only, the Value side for the tokens
+  // [v_tok_a, v_tok_b) only; everything else in the records is left as it is.
+  int k_tile_a, k_tile_b, v_tok_a, v_tok_b;
 };
 
 struct DequantArgs {
   const uint32_t* packed;
-  float* out; int tiles_cap; int n_tiles; int k_bits; int v_bits; int which;
+  float* out; int tiles_cap; int n_tokens; int k_bits; int v_bits; int which;   // out: [units][n_tokens][128]
 };
 
 struct AppendArgs {
@@ -100,7 +130,8 @@ struct AttnArgs {
   const uint16_t* k_new; const uint16_t* v_new;
   uint16_t* k_win_w; uint16_t* v_win_w;
   int new_slot;           // -1: nothing to append
-  float* part;            // split partials: [units][n_splits][G][kD + 2]
+  float* part;            // partials: [units][n_parts][G][kD + 2], the first n_splits of a unit written by this launch
+  int n_parts;            // n_splits, plus one when an earlier launch left the partial of the tokens between two fronts
   uint32_t* counters;     // [units] arrival counters (zero before and after every call)
   int tiles_cap, W_cap, n_tiles, n_w, w0;
   int Hq, Hkv, n_splits;
@@ -108,8 +139,25 @@ struct AttnArgs {
   float scale_log2;       // softmax_scale * log2(e)
 };
 
+// Tokens [t_begin, t_end) of every unit, each Key and each Value from where it lives (packed before its front, the
+// fp16 ring from it on): one partial (reference, sum of numerators, unnormalized output) per (unit, head) into
+// slot part_index of the partials array.
+struct MixedArgs {
+  const uint16_t* q; const uint32_t* packed; const uint16_t* k_win; const uint16_t* v_win;
+  float* part; int n_parts, part_index;
+  int tiles_cap, W_cap, k_bits, v_bits;
+  int n_qk, n_qv;          // the two fronts
+  int t_begin, t_end;      // t_begin is a multiple of 32
+  int slot_begin;          // ring slot of token t_begin
+  int G;                   // heads per workgroup (at most 8)
+  float scale_log2;
+};
+
 hipError_t launch_quantize_pack(const QuantArgs& a, int k_bits, int v_bits,
                                 int n_tiles, int units, hipStream_t s);
+hipError_t launch_quantize_fronts(const QuantArgs& a, int k_bits, int v_bits,
+                                  int n_tiles, int units, hipStream_t s);
+hipError_t launch_mixed_fronts(const MixedArgs& a, int units, int head_blocks, hipStream_t s);
 hipError_t launch_dequant(const DequantArgs& a, int units, hipStream_t s);
 hipError_t launch_append(const AppendArgs& a, hipStream_t s);
 hipError_t launch_stream_read(const void* buf, size_t bytes, int workgroups, int threads, uint32_t* sink, hipStream_t s);

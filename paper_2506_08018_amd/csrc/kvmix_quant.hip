@@ -81,9 +81,22 @@ template <int BITS> constexpr int acc_words() { return BITS == 4 ? 32 : 16; }
 // Final step shared by both waves: `w` holds, in every lane of a quad (q = lane & 3), the complete words
 // i = 0..15 (per chunk) of column group (kq, j); lane q stores the words i = 4q .. 4q+3. `hi` (3-bit only)
 // holds the high-plane words, complete in both lanes j and j^1; the even-j lanes store them.
-template <int BITS>
+// A word of which only the bits of `mask` are this launch's to write (PARTIAL: Values that leave the window token
+// by token share their words with the neighbouring tokens' codes, which are already in place or still to come).
+// No other lane of the launch touches the word, and launches on one cache are ordered by the caller's stream.
+template <bool PARTIAL>
+__device__ __forceinline__ void put_word(uint32_t* p, uint32_t v, uint32_t mask) {
+  if constexpr (!PARTIAL) {
+    *p = v;
+  } else {
+    if (mask == 0xFFFFFFFFu) *p = v;
+    else if (mask != 0u) *p = (*p & ~mask) | (v & mask);
+  }
+}
+
+template <int BITS, bool PARTIAL = false>
 __device__ __forceinline__ void store_words(uint32_t* sec, const uint32_t (&w)[acc_words<BITS>()], const uint32_t (&hi)[16],
-                                            int kq, int j, int q) {
+                                            int kq, int j, int q, uint32_t wmask = 0xFFFFFFFFu, uint32_t hmask = 0xFFFFFFFFu) {
   constexpr int kChunks = BITS == 4 ? 2 : BITS == 1 ? 0 : 1;
   constexpr int kPlane = BITS == 1 ? 0 : 256;     // first word of the 1-bit plane
 #pragma unroll
@@ -91,14 +104,14 @@ __device__ __forceinline__ void store_words(uint32_t* sec, const uint32_t (&w)[a
 #pragma unroll
     for (int n = 0; n < 4; n++) {
       const uint32_t v = q == 0 ? w[16 * c + n] : q == 1 ? w[16 * c + 4 + n] : q == 2 ? w[16 * c + 8 + n] : w[16 * c + 12 + n];
-      sec[256 * c + 4 * (16 * kq + 4 * q + n) + j] = v;
+      put_word<PARTIAL>(sec + 256 * c + 4 * (16 * kq + 4 * q + n) + j, v, wmask);
     }
   if constexpr (BITS == 3 || BITS == 1) {
     if ((j & 1) == 0) {
 #pragma unroll
       for (int n = 0; n < 4; n++) {
         const uint32_t v = q == 0 ? hi[n] : q == 1 ? hi[4 + n] : q == 2 ? hi[8 + n] : hi[12 + n];
-        sec[kPlane + 2 * (16 * kq + 4 * q + n) + (j >> 1)] = v;
+        put_word<PARTIAL>(sec + kPlane + 2 * (16 * kq + 4 * q + n) + (j >> 1), v, hmask);
       }
     }
   }
@@ -123,12 +136,26 @@ __device__ __forceinline__ const uint16_t* source_row(const uint16_t* ring, cons
   return in + unit_off + (int64_t)(r - a.n_ring) * tok;
 }
 
-template <int KB, int VB>
+// Row r of an ageing launch (PARTIAL): always a ring slot; the launch may span more rows than the ring has slots
+// (only rows of live tokens are read).
+__device__ __forceinline__ const uint16_t* ring_row(const uint16_t* ring, const QuantArgs& a, int u, int r) {
+  const int slot = (a.ring_w0 + r) % a.W_cap;
+  return ring + ((size_t)u * a.W_cap + slot) * kD;
+}
+
+// PARTIAL: ageing with separate fronts for Keys and Values. The Key wave works on the tiles [k_tile_a, k_tile_b)
+// only; the Value wave writes the codes and metadata of the tokens [v_tok_a, v_tok_b) only, merging them into
+// words that it shares with other tokens.
+template <int KB, int VB, bool PARTIAL>
 __global__ __launch_bounds__(128) void quantize_pack_kernel(QuantArgs a) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int kq = lane >> 4, j = (lane >> 2) & 3, q = lane & 3;
   const int tile_in = blockIdx.x, jh = blockIdx.y, b = blockIdx.z;   // no integer division at the start of a short kernel
   const int u = b * a.Hkv + jh;
+  if constexpr (PARTIAL) {
+    const int tile_abs = a.tile0 + tile_in;
+    if (wave == 0 && (tile_abs < a.k_tile_a || tile_abs >= a.k_tile_b)) return;   // wave-uniform; the waves never synchronize
+  }
   uint32_t* rec = a.packed + ((size_t)u * a.tiles_cap + (size_t)(a.tile0 + tile_in)) * record_words(KB, VB);
   uint32_t hi[16];
 #pragma unroll
@@ -139,7 +166,10 @@ __global__ __launch_bounds__(128) void quantize_pack_kernel(QuantArgs a) {
     const int d0 = 32 * q + 8 * kq + 2 * j;
     uint32_t xw[kTile];                              // (x[tau][d0], x[tau][d0 + 1])
 #pragma unroll
-    for (int t = 0; t < kTile; t++) xw[t] = *reinterpret_cast<const uint32_t*>(source_row(a.k_ring, a.k, a.k_tok, k_off, a, u, tile_in * kTile + t) + d0);
+    for (int t = 0; t < kTile; t++) {
+      const uint16_t* rowp = PARTIAL ? ring_row(a.k_ring, a, u, tile_in * kTile + t) : source_row(a.k_ring, a.k, a.k_tok, k_off, a, u, tile_in * kTile + t);
+      xw[t] = *reinterpret_cast<const uint32_t*>(rowp + d0);
+    }
     half2_t mn2 = as_half2(xw[0]), mx2 = mn2;
 #pragma unroll
     for (int t = 1; t < kTile; t++) {
@@ -196,11 +226,24 @@ __global__ __launch_bounds__(128) void quantize_pack_kernel(QuantArgs a) {
     const int64_t v_off = b * a.v_unit_b + jh * a.v_unit_h;
     const int tau0 = 8 * kq + 2 * j;
     u32x4_t xr[2][4];                                // rows tau0, tau0 + 1: channels 32*q .. 32*q + 31
+    // PARTIAL: which of the lane's two tokens, and of the two of lane j ^ 1, are among those that leave now
+    auto leaves = [&](int tau) { const int t = (a.tile0 + tile_in) * kTile + tau; return !PARTIAL || (t >= a.v_tok_a && t < a.v_tok_b); };
+    const bool mine[2] = {leaves(tau0), leaves(tau0 + 1)};
 #pragma unroll
     for (int hh = 0; hh < 2; hh++)
 #pragma unroll
-      for (int c = 0; c < 4; c++)
-        xr[hh][c] = *reinterpret_cast<const u32x4_t*>(source_row(a.v_ring, a.v, a.v_tok, v_off, a, u, tile_in * kTile + tau0 + hh) + 32 * q + 8 * c);
+      for (int c = 0; c < 4; c++) {
+        xr[hh][c] = u32x4_t{0, 0, 0, 0};
+        if (mine[hh]) {
+          const uint16_t* rowp = PARTIAL ? ring_row(a.v_ring, a, u, tile_in * kTile + tau0 + hh) : source_row(a.v_ring, a.v, a.v_tok, v_off, a, u, tile_in * kTile + tau0 + hh);
+          xr[hh][c] = *reinterpret_cast<const u32x4_t*>(rowp + 32 * q + 8 * c);
+        }
+      }
+    const uint32_t wmask = (mine[0] ? 0x0000FFFFu : 0u) | (mine[1] ? 0xFFFF0000u : 0u);
+    // a plane word holds the pairs j (even, bits 0-7 and 16-23) and j + 1 (bits 8-15 and 24-31); the even lane stores it
+    uint32_t hmask = (mine[0] ? 0x000000FFu : 0u) | (mine[1] ? 0x00FF0000u : 0u);
+    if constexpr (PARTIAL) hmask |= (leaves(tau0 + 2) ? 0x0000FF00u : 0u) | (leaves(tau0 + 3) ? 0xFF000000u : 0u);
+    else hmask = 0xFFFFFFFFu;
     GroupParams gp[2];
 #pragma unroll
     for (int hh = 0; hh < 2; hh++) {
@@ -214,8 +257,16 @@ __global__ __launch_bounds__(128) void quantize_pack_kernel(QuantArgs a) {
       gp[hh] = group_params<VB>(mn, mx);
     }
     // metadata word 4*(16*g + tau0/2) + f: scale pair (f = 2), minimum pair (f = 3)
-    *reinterpret_cast<u32x2_t*>(rec + 4 * (16 * q + (tau0 >> 1)) + 2) =
-        u32x2_t{(uint32_t)gp[0].scale_h | ((uint32_t)gp[1].scale_h << 16), (uint32_t)gp[0].zero_h | ((uint32_t)gp[1].zero_h << 16)};
+    {
+      const uint32_t sc2 = (uint32_t)gp[0].scale_h | ((uint32_t)gp[1].scale_h << 16), zp2 = (uint32_t)gp[0].zero_h | ((uint32_t)gp[1].zero_h << 16);
+      uint32_t* mp = rec + 4 * (16 * q + (tau0 >> 1)) + 2;
+      if constexpr (!PARTIAL) {
+        *reinterpret_cast<u32x2_t*>(mp) = u32x2_t{sc2, zp2};
+      } else {
+        put_word<true>(mp, sc2, wmask);
+        put_word<true>(mp + 1, zp2, wmask);
+      }
+    }
     // partial words with the lane-independent shifts first (fields of slot parity e/16 and token parity hh)
     uint32_t pw[16], ph[16];
 #pragma unroll
@@ -279,37 +330,18 @@ __global__ __launch_bounds__(128) void quantize_pack_kernel(QuantArgs a) {
         }
       }
     }
-    store_words<VB>(rec + kMetaWords + tile_words(KB), w, hi, kq, j, q);
+    store_words<VB, PARTIAL>(rec + kMetaWords + tile_words(KB), w, hi, kq, j, q, wmask, hmask);
   }
 }
 
-// x = code * s_i + min, evaluated in fp32 (multiply, then add).
+// x = code * s_i + min, evaluated in fp32 (multiply, then add), of the first n_tokens tokens of every unit.
 __global__ __launch_bounds__(256) void dequant_kernel(DequantArgs a) {
   const int u = blockIdx.y, tile_i = blockIdx.x;
   const uint32_t* rec = a.packed + ((size_t)u * a.tiles_cap + tile_i) * record_words(a.k_bits, a.v_bits);
-  const uint16_t* meta = reinterpret_cast<const uint16_t*>(rec);
-  const int bits = a.which ? a.v_bits : a.k_bits;
-  const uint32_t* words = rec + kMetaWords + (a.which ? tile_words(a.k_bits) : 0);
   for (int e = threadIdx.x; e < kTile * kD; e += blockDim.x) {
     const int tau = e / kD, d = e % kD;
-    int l, j, hh, slot, gi, ms, mz;
-    if (a.which == 0) {
-      const int ks = d / 32, kq = (d % 32) / 8, m = (tau % 8) / 4, i = 4 * (tau / 8) + tau % 4;
-      l = 16 * kq + i; j = (d % 8) / 2; hh = d % 2; slot = ks + 4 * m;
-      ms = key_meta_half(d, 0); mz = key_meta_half(d, 1); gi = tau;
-    } else {
-      l = 16 * (tau / 8) + d % 16; j = (tau % 8) / 2; hh = tau % 2; slot = d / 16;
-      ms = value_meta_half(tau, d / 32, 0); mz = value_meta_half(tau, d / 32, 1); gi = d % 32;
-    }
-    const CodePos p = pos_from_slots(bits, l, j, hh, slot);
-    int code;
-    if (bits == 3) code = ((words[p.word] >> p.bit) & 3u) + 4 * ((words[p.hword] >> p.hbit) & 1u);
-    else code = (words[p.word] >> p.bit) & ((1u << bits) - 1u);
-    const float s = (float)__builtin_bit_cast(half_t, meta[ms]);
-    const float mn = (float)__builtin_bit_cast(half_t, meta[mz]);
-    const float si = (bits == 3 && (gi == 10 || gi == 21)) ? (s * 7.0f) / 3.0f : s;
-    const float prod = (float)code * si;
-    a.out[((size_t)u * a.n_tiles + tile_i) * kTile * kD + e] = prod + mn;
+    const int t = tile_i * kTile + tau;
+    if (t < a.n_tokens) a.out[((size_t)u * a.n_tokens + t) * kD + d] = dequant_elem(rec, a.k_bits, a.v_bits, a.which, tau, d);
   }
 }
 
@@ -342,9 +374,9 @@ __global__ __launch_bounds__(768) void stream_read_kernel(const u32x4_t* buf, si
   if ((acc[0] & acc[1] & acc[2] & acc[3]) == 0xFFFFFFFFu && sink) sink[0] = 1u;
 }
 
-template <int KB, int VB>
+template <int KB, int VB, bool PARTIAL = false>
 hipError_t launch_qp(const QuantArgs& a, dim3 grid, hipStream_t s) {
-  quantize_pack_kernel<KB, VB><<<grid, 128, 0, s>>>(a);
+  quantize_pack_kernel<KB, VB, PARTIAL><<<grid, 128, 0, s>>>(a);
   return hipGetLastError();
 }
 
@@ -375,9 +407,34 @@ hipError_t launch_quantize_pack(const QuantArgs& a, int k_bits, int v_bits,
   return hipErrorInvalidValue;
 }
 
+hipError_t launch_quantize_fronts(const QuantArgs& a, int k_bits, int v_bits,
+                                  int n_tiles, int units, hipStream_t s) {
+  if (n_tiles == 0 || units == 0) return hipSuccess;
+  const dim3 grid(n_tiles, a.Hkv, units / a.Hkv);
+  switch (k_bits * 10 + v_bits) {
+    case 11: return launch_qp<1, 1, true>(a, grid, s);
+    case 12: return launch_qp<1, 2, true>(a, grid, s);
+    case 13: return launch_qp<1, 3, true>(a, grid, s);
+    case 14: return launch_qp<1, 4, true>(a, grid, s);
+    case 21: return launch_qp<2, 1, true>(a, grid, s);
+    case 31: return launch_qp<3, 1, true>(a, grid, s);
+    case 41: return launch_qp<4, 1, true>(a, grid, s);
+    case 22: return launch_qp<2, 2, true>(a, grid, s);
+    case 23: return launch_qp<2, 3, true>(a, grid, s);
+    case 24: return launch_qp<2, 4, true>(a, grid, s);
+    case 32: return launch_qp<3, 2, true>(a, grid, s);
+    case 33: return launch_qp<3, 3, true>(a, grid, s);
+    case 34: return launch_qp<3, 4, true>(a, grid, s);
+    case 42: return launch_qp<4, 2, true>(a, grid, s);
+    case 43: return launch_qp<4, 3, true>(a, grid, s);
+    case 44: return launch_qp<4, 4, true>(a, grid, s);
+  }
+  return hipErrorInvalidValue;
+}
+
 hipError_t launch_dequant(const DequantArgs& a, int units, hipStream_t s) {
-  if (a.n_tiles == 0 || units == 0) return hipSuccess;
-  dequant_kernel<<<dim3(a.n_tiles, units), 256, 0, s>>>(a);
+  if (a.n_tokens == 0 || units == 0) return hipSuccess;
+  dequant_kernel<<<dim3((a.n_tokens + kTile - 1) / kTile, units), 256, 0, s>>>(a);
   return hipGetLastError();
 }
 
