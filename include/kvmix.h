@@ -46,8 +46,8 @@
  *     Key code (tau, d):   ks = d/32, kq = (d%32)/8, j = (d%8)/2, hh = d%2,
  *                          m = (tau%8)/4, i = 4*(tau/8) + tau%4, slot = ks + 4*m
  *     Value code (tau, d): kq = tau/8, j = (tau%8)/2, hh = tau%2, i = d%16, slot = d/16
- *     1-bit: word 2*l + j/2, bit 16*hh + 8*(j%2) + 2*(slot%4) + slot/4 (32 codes per word; the group's
- *            range must be representable in fp16, it is the stored scale).
+ *     1-bit: word 2*l + j/2, bit 16*hh + 8*(j%2) + 2*(slot%4) + slot/4 (32 codes per word; the stored scale
+ *            is the group's range).
  *     2-bit: word 4*l + j, bits [16*hh + 2*slot, +2).
  *     4-bit: word 256*(slot/4) + 4*l + j, bits [16*hh + 4*(slot%4), +4).
  *     3-bit: code = lo + 4*hi. The 2-bit plane `lo` is stored exactly like a 2-bit section
@@ -76,11 +76,12 @@
  *
  * Numeric preconditions (not checked on the device)
  *   - all K / V / q inputs are finite (Sec. 3.2.2 defines the quantizer on real numbers only);
- *   - 1-bit groups: max - min of a group must be <= 65504, because the stored fp16 scale is the range
- *     itself (with 2-4 bits the scale (max - min)/q_max of finite fp16 inputs is always representable);
+ *   - the quantizer is total on finite inputs: with 2-4 bits the scale (max - min)/q_max of fp16 inputs is always
+ *     an fp16 number; a 1-bit scale (the range itself) that exceeds 65504 is stored as 65504 (the codes are taken
+ *     against that stored scale, so the upper level dequantizes to min + 65504);
  *   - attention folds q*scale products into fp16 matrix-core operands: |q[h][d]| * s[d] < 16384 for every
- *     Key group scale s[d] and every Value scale times a softmax weight <= 1, i.e. s < 16384; both hold
- *     for any cache whose values stay below ~10^4 in magnitude at |q| <= 8.
+ *     Key group scale s[d], and softmax numerators of up to 64 times a Value group scale: s < 1024 for every
+ *     Value scale; both hold for any cache whose values stay below ~10^3 in magnitude at |q| <= 8.
  */
 #ifndef KVMIX_H_
 #define KVMIX_H_
@@ -181,7 +182,7 @@ int kvmix_workspace_bytes(const kvmix_shape* shape, int T_max, size_t* bytes);
  * of 8). Per group: mn/mx by fp16 comparison; s = fp16((mx - mn) / qmax) with fp32
  * arithmetic; code = clamp(rint((x - mn) / s_i), 0, qmax_i) in fp32 with round-half-even,
  * where for 3 bit the in-group elements 10 and 21 use qmax_i = 3 and s_i = (s*7)/3;
- * a zero scale gives all-zero codes and is stored as +0; the stored zero-point is mn (-0 stored as +0).
+ * a zero scale gives all-zero codes and is stored as +0; a 1-bit scale above 65504 is stored as 65504; the stored zero-point is mn (-0 stored as +0).
  * Does not touch n_q / n_w (the caller sets cache->n_q). Inputs must be finite. */
 int kvmix_quantize_pack(const kvmix_shape* shape, const kvmix_layer_cfg* cfg,
                         const uint16_t* k_fp16, const uint16_t* v_fp16,

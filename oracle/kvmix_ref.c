@@ -7,8 +7,8 @@
  *
  * What it computes
  *   - the group-wise asymmetric quantizer of Sec. 3.2.2 at 1, 2, 3 and 4 bits (steps 1-4 and the q_max case
- *     equation for 3-bit blocks of 11; with 1 bit the stored step is the group's range, which must be
- *     representable in fp16), with Keys grouped per channel and Values per token
+ *     equation for 3-bit blocks of 11; with 1 bit the stored step is the group's range, stored as 65504 when
+ *     it exceeds the fp16 range), with Keys grouped per channel and Values per token
  *     (Sec. 3.2.1), group size 32 (Sec. 4.2);
  *   - the packed-cache encoding (bit positions documented in pos_key / pos_value, the tile
  *     record in the section "tile records" below);
@@ -122,6 +122,7 @@ void kvmix_ref_quantize_group(const uint16_t* x, int bits, uint8_t* code, uint16
   if (range == 0.0f) range = 0.0f * 0.0f;           /* a zero-range group stores scale +0 whatever the signs of its zeros */
   float s32 = range / (float)qmax_of(bits);
   *scale_h = f2h(s32);
+  if (*scale_h == 0x7C00) *scale_h = 0x7BFF;        /* a step beyond the fp16 range (1 bit only: the step is the range itself) is stored as the largest fp16 number */
   *zero_h = f2h(mn);                                /* exact: mn is an fp16 value */
   float s = h2f(*scale_h);
   for (int i = 0; i < GROUP; i++) {

@@ -37,7 +37,8 @@ __device__ __forceinline__ GroupParams group_params(float mn, float mx) {
   float range = mx - mn;
   if (range == 0.0f) range = 0.0f;                // a zero-range group stores scale +0 whatever the signs of its zeros
   const float s32 = range / (float)((1 << BITS) - 1);
-  const half_t sh = (half_t)s32;                  // round-to-nearest-even
+  // round-to-nearest-even; a 1-bit step (the range itself) beyond the fp16 range is stored as the largest fp16 number
+  const half_t sh = (half_t)(BITS == 1 ? fminf(s32, 65504.0f) : s32);
   g.mn = mn;
   g.s = (float)sh;
   g.scale_h = __builtin_bit_cast(uint16_t, sh);

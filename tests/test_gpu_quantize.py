@@ -36,7 +36,7 @@ def adversarial_kv(seed, B, Hkv, T):
     return k.astype(np.float16), v.astype(np.float16)
 
 
-@pytest.mark.parametrize("kb,vb", [(2, 2), (3, 3), (4, 4)])
+@pytest.mark.parametrize("kb,vb", [(2, 2), (3, 3), (4, 4), (1, 1), (1, 4), (3, 1)])   # 1 bit: ranges beyond fp16 store the largest fp16 step
 def test_quantize_pack_adversarial_groups(kb, vb):
     print(f"case adversarial kb={kb} vb={vb}", flush=True)
     B, Hkv, T = 1, 2, 256

@@ -153,3 +153,23 @@ def test_extreme_range(ref):
         assert np.isfinite(s) and codes[0] == 0 and codes[1] == 2 ** bits - 1
         step = np.where(qmax_i(bits) == 2 ** bits - 1, s, s * 7 / 3)
         assert np.all(np.abs(deq - x) <= step / 2 * 1.001)
+
+
+def test_one_bit_range_beyond_fp16_is_stored_as_largest_fp16(ref):
+    """With one bit the step is the range itself (Sec. 3.2.2 step 1 with q_max = 1), and fp16 inputs can span up to
+    2 * 65504: such a step is stored as 65504, the codes are taken against the stored step (every element at or
+    above min + 65504/2 gets code 1), and everything stays finite; the lower half keeps its exact level."""
+    for lo, hi in ((-65504.0, 65504.0), (-40000.0, 30000.0), (-1.0, 65504.0), (0.0, 65504.0)):
+        x = np.linspace(lo, hi, 32)
+        codes, s, z, deq = run(ref, f16(x), 1)
+        xr = f16(x).astype(np.float64)
+        rng = xr.max() - xr.min()
+        assert s == min(float(np.float16(min(rng, 65504.0))), 65504.0) and z == xr.min()
+        assert np.all(np.isfinite(deq))
+        t = (xr - xr.min()) / s
+        want = np.clip(np.rint(t.astype(np.float32)), 0, 1)
+        assert np.array_equal(codes, want.astype(int))
+        assert codes[0] == 0 and codes[-1] == 1
+        assert np.all(deq[codes == 0] == xr.min()) and np.all(deq[codes == 1] == xr.min() + s)
+    # 2-4 bits: the largest possible range over q_max is always an fp16 number (no saturation to test)
+    assert 2 * 65504.0 / 3 < 65504.0
