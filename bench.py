@@ -74,7 +74,7 @@ def build_layers(cfg, device, seed):
     prefill_s = 0.0
     for l in range(L):
         lc = kv.LayerCfg(int(kbits[l]), int(vbits[l]), W)
-        cache = kv.LayerCache(shape, lc, T_cap=T + 64, W_cap=W + 32, device=device)
+        cache = kv.LayerCache(shape, lc, T_cap=T + synth.GEN_ROOM, W_cap=W + 32, device=device)
         q, k, v = synth.gen_layer_torch(device, seed, l, B, Hq, Hkv, n_q0 + n_w0)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
@@ -160,7 +160,7 @@ def measure(name, steps, warmup, seed, n_splits, device, cpu_s):
     L, B, Hq, Hkv = cfg["L"], cfg["B"], cfg["Hq"], cfg["Hkv"]
     units = B * Hkv
     shape, layers, kbits, vbits, prefill = build_layers(cfg, device, seed)
-    ws = torch.zeros(kv.workspace_bytes(shape, cfg["T"] + 64), dtype=torch.uint8, device=device)
+    ws = torch.zeros(kv.workspace_bytes(shape, cfg["T"] + synth.GEN_ROOM), dtype=torch.uint8, device=device)
     g = torch.Generator(device=device)
     g.manual_seed(seed + 77)
     n_new = steps + warmup + 1
@@ -261,11 +261,110 @@ def measure(name, steps, warmup, seed, n_splits, device, cpu_s):
     return res
 
 
+def widened_rows(device, seed):
+    """Short timings of the calls beyond the headline step, one layer each at the headline's batch and context:
+    multi-query attention (71 query heads padded to 72 on one kv head), a 4096-token chunk through kvmix_append_tokens,
+    and attention on a cache whose Keys and Values age at fronts of their own."""
+    import torch
+    import paper_2506_08018_amd as kv
+    out = {}
+    hstream = torch.cuda.current_stream().cuda_stream
+
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps * 1e3      # microseconds per call
+
+    c2 = synth.CONFIGS[HEADLINE]
+    T, W = c2["T"], c2["W"]
+    # -- multi-query attention: B = 32 sequences, 72 query heads on 1 kv head, 4 layers in rotation
+    B, Hq, Hkv = 32, 72, 1
+    shape, lc = kv.Shape(B, Hq, Hkv), kv.LayerCfg(2, 2, W)
+    n_w, n_q = W + 24, T - 8 - (W + 24)
+    caches = []
+    for l in range(4):
+        c = kv.LayerCache(shape, lc, T + synth.GEN_ROOM, W + 32, device=device)
+        q, k, v = synth.gen_layer_torch(device, seed, 100 + l, B, Hq, Hkv, n_q + n_w)
+        kv.quantize_pack(shape, lc, k[:, :, :n_q], v[:, :, :n_q], c)
+        c.set_window(k[:, :, n_q:], v[:, :, n_q:])
+        caches.append(c)
+        del k, v
+    o = torch.zeros_like(q)
+    ws = torch.zeros(kv.workspace_bytes(shape, T + synth.GEN_ROOM), dtype=torch.uint8, device=device)
+    state = {"i": 0}
+
+    def mqa():
+        kv.decode_attn(shape, lc, q, caches[state["i"] % 4], o, ws, stream=hstream)
+        state["i"] += 1
+    us = timed(mqa, 80)
+    nb = algorithmic_bytes(B * Hkv, n_q, n_w, 2, 2)
+    out["mqa_72_heads_1_kv_head"] = {"batch": B, "q_heads": Hq, "kv_heads": Hkv, "context": n_q + n_w, "bits": "2/2", "launch_us": us,
+                                      "bytes_per_launch": nb, "hbm_gbs": nb / us / 1e3, "frac_of_peak": nb / us / 1e3 / HBM_PEAK_GBS,
+                                      "note": "9 head blocks per unit read the same records: bytes counted once"}
+    del caches, ws
+    # -- one 4096-token chunk of new tokens through kvmix_append_tokens (chunked prefill) at the headline shape
+    B, Hq, Hkv = c2["B"], c2["Hq"], c2["Hkv"]
+    shape, lc = kv.Shape(B, Hq, Hkv), kv.LayerCfg(2, 2, W)
+    n_chunk = 4096
+    c = kv.LayerCache(shape, lc, 2 * n_chunk + 64, W + 32, device=device)
+    _, k, v = synth.gen_layer_torch(device, seed, 200, B, Hq, Hkv, n_chunk)
+
+    def chunk():
+        c.c.n_q, c.c.n_w, c.c.w0 = 0, 0, 0
+        kv.append_tokens(shape, lc, k, v, c)
+    us = timed(chunk, 10)
+    elems = B * Hkv * n_chunk * 128
+    moved = elems * (4 + (2 + 2 + 2) / 8.0)
+    out["append_tokens_4096_chunk"] = {"batch": B, "kv_heads": Hkv, "tokens": n_chunk, "bits": "2/2", "launches": 2, "ms": us / 1e3,
+                                        "hbm_gbs": moved / us / 1e3, "frac_of_peak": moved / us / 1e3 / HBM_PEAK_GBS}
+    del c, k, v
+    # -- attention with the Value front ahead of the Key front (Sec. 3.3 ratios 20 % / 10 %): 4 layers in rotation
+    lc = kv.LayerCfg(3, 2, -1)
+    caches = []
+    Wc = 1024
+    for l in range(4):
+        c = kv.LayerCache(shape, lc, T + synth.GEN_ROOM, Wc, device=device)
+        q, k, v = synth.gen_layer_torch(device, seed, 300 + l, B, Hq, Hkv, T)
+        head_len = T - Wc + 32
+        kv.quantize_pack(shape, lc, k[:, :, :head_len], v[:, :, :head_len], c)
+        kv.append_tokens(shape, lc, k[:, :, head_len:], v[:, :, head_len:], c)
+        keep_k, keep_v = kv.rpc_next(0.2, 0.1, T, T)
+        kv.flush(shape, lc, c, keep_k, keep_v)
+        caches.append(c)
+        del k, v
+    o = torch.zeros_like(q)
+    ws = torch.zeros(kv.workspace_bytes(shape, T + synth.GEN_ROOM), dtype=torch.uint8, device=device)
+    state["i"] = 0
+
+    def fronts():
+        kv.decode_attn(shape, lc, q, caches[state["i"] % 4], o, ws, stream=hstream)
+        state["i"] += 1
+    us = timed(fronts, 80)
+    c = caches[0]
+    units = B * Hkv
+    nb = units * (c.n_q * (16 * 3 + 16) + c.n_qv * (16 * 2 + 16) + (c.n - c.n_q) * 256 + (c.n - c.n_qv) * 256)
+    out["fronts_apart_r_0.2_0.1"] = {"batch": B, "kv_heads": Hkv, "context": c.n, "bits": "3/2", "key_front": c.n_q, "value_front": c.n_qv,
+                                      "launches": 2, "us_per_call": us, "bytes_per_call": nb, "hbm_gbs": nb / us / 1e3,
+                                      "frac_of_peak": nb / us / 1e3 / HBM_PEAK_GBS}
+    del caches, ws
+    torch.cuda.empty_cache()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    # defaults: the caches start 8 steps before a flush, so steps 40..71 hold exactly one flush step in 32 (its natural
+    # rate); 40 warmup steps (30 ms) because the first steps after the set-up run measurably slower (5 warmup steps:
+    # 0.78 ms per step, 40: 0.73 ms)
+    ap.add_argument("--steps", type=int, default=32)
+    ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--config", default=HEADLINE, choices=sorted(synth.CONFIGS))
     ap.add_argument("--seed", type=int, default=synth.BASE_SEED)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -291,7 +390,7 @@ def main():
     others = {}
     if not args.no_other_configs and args.config == HEADLINE:
         # short runs of the other workloads (parity-test cases, not bench lines): each long enough to contain the flush
-        plan = {"cfg1_single_layer": (40, 10), "cfg3_mistral_7b_gqa": (12, 2), "cfg4_llama3_8b_long": (16, 2), "cfg5_70b_stress": (16, 2)}
+        plan = {"cfg1_single_layer": (64, 40), "cfg3_mistral_7b_gqa": (32, 40), "cfg4_llama3_8b_long": (32, 40), "cfg5_70b_stress": (16, 24)}
         for name, (st, wu) in plan.items():
             try:
                 r = measure(name, st, wu, args.seed, 0, device, 0.0 if args.no_cpu_baseline else 3.0)
@@ -300,6 +399,12 @@ def main():
                 others[name] = r
             except Exception as e:  # noqa: BLE001  (a failing side run must not take the headline down)
                 others[name] = {"error": f"{type(e).__name__}: {e}"}
+
+    if not args.no_other_configs and args.config == HEADLINE:
+        try:
+            others["widened"] = widened_rows(device, args.seed)
+        except Exception as e:  # noqa: BLE001
+            others["widened"] = {"error": f"{type(e).__name__}: {e}"}
 
     if args.calibrate_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device=device)   # 1 GiB read, 1 GiB written per call

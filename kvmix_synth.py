@@ -9,6 +9,10 @@ prompts; no model weights or benchmark text are involved.
 import numpy as np
 
 BASE_SEED = 2506
+# Packed-cache capacity of the benchmark caches beyond the context length T: room for this many generated tokens
+# (a multiple of 32). The tile count per unit sets the address stride between units, which the memory system is
+# sensitive to (one stride measured 25 % slower than its neighbours); capacity is the caller's choice.
+GEN_ROOM = 320
 OUTLIER_CHANNELS = 4
 OUTLIER_GAIN = 10.0
 

@@ -292,13 +292,21 @@ int plan_attention(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const uint
   const int n_items = c->W_cap / kTile + fr.packed_tiles;
   if (n_splits < 0 || n_splits > max_splits(sh)) return KVMIX_ERR_BAD_SHAPE;
   if (n_splits == 0) {
-    // one workgroup occupies a whole compute unit (LDS): aim at one workgroup per unit, at least 8 tiles each
+    // One workgroup occupies a whole compute unit (LDS), so the launch runs in rounds of `cus` workgroups. A round
+    // costs a fixed part (start, merge of the waves, partial and arrival: about what 48 tiles take) plus the tiles
+    // of one split; take the split count with the smallest rounds x (48 + tiles per split), at least 8 tiles each.
     const int cus = num_cus();
     if (cus == 0) return hip_fail(hipErrorInvalidDevice);
-    n_splits = cus / out_units(sh);
-    if (n_splits > n_items / 8) n_splits = n_items / 8;
-    if (n_splits > max_splits(sh)) n_splits = max_splits(sh);
-    if (n_splits < 1) n_splits = 1;
+    const int ou = out_units(sh);
+    int s_max = n_items / 8;
+    if (s_max > max_splits(sh)) s_max = max_splits(sh);
+    double best = 0.0;
+    n_splits = 1;
+    for (int s = 1; s <= s_max || s == 1; s++) {
+      const double rounds = (double)(((long long)ou * s + cus - 1) / cus);
+      const double cost = rounds * (48.0 + (double)n_items / s);
+      if (s == 1 || cost < best) { best = cost; n_splits = s; }
+    }
   }
   if (n_splits > n_items) n_splits = n_items;
   AttnArgs a{};

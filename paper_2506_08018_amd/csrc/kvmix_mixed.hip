@@ -3,19 +3,21 @@
 // differ; Sec. 3.2.2 step 4 for the dequantization).
 //
 // The main attention kernel works on tiles whose Keys and Values are both packed and on window tiles whose Keys and
-// Values are both fp16. The tokens in between (a few tiles: at most the window's capacity) have one side packed and
-// the other in the ring, and the Value front may stand inside a tile. This kernel takes them token by token, each
-// Key row and each Value row from where it lives, in plain fp32 on the vector unit, and leaves one partial
-// (reference maximum, sum of numerators, unnormalized output; log2 domain like the main kernel's partials) per
-// (unit, head) in the partials array, where the main launch's split merge picks it up. It is launched before the
-// main kernel on the same stream.
+// Values are both fp16. The tokens in between ((r_k - r_v) x context of them under the count formula) have one
+// side packed and the other in the ring, and the Value front may stand inside a tile. This kernel takes them tile by
+// tile: a wave turns the tile's Key rows into fp32 in its own LDS area (from the packed record: every lane unpacks
+// the 64 codes of its 16-byte column, x = code * s_i + min; or from the fp16 ring), takes the scores and the softmax
+// numerators on the vector unit, then does the same with the Value rows. It leaves one partial (reference maximum,
+// sum of numerators, unnormalized output; log2 domain like the main kernel's partials) per (unit, head) in the
+// partials array, where the main launch's split merge picks it up. It is launched before the main kernel on the
+// same stream. The vector unit is enough here: the range is a small part of the context and its bytes are few.
 #include "kvmix_common.hpp"
 
 namespace kvmix {
 
 namespace {
 
-constexpr int kMixWaves = 4;
+constexpr int kMixWaves = 8;
 constexpr int kPitch = kD + 4;   // floats per staged row: rows of neighbouring tokens start 4 banks apart
 constexpr int kHeads = 8;        // heads per workgroup at most
 
@@ -35,13 +37,53 @@ __device__ __forceinline__ void wave_fence() {
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
+__device__ __forceinline__ float h2f(uint32_t pair, int hh) { return (float)__builtin_bit_cast(half_t, (uint16_t)(pair >> (16 * hh))); }
 
+// The 64 codes of 16-byte column l of a code section: (word j, half hh, slot) -> code.
+template <int BITS> struct Column {
+  uint32_t w[BITS == 4 ? 8 : 4];
+  uint32_t h[2];
+  __device__ __forceinline__ void load(const uint32_t* sec, int l) {
+    if constexpr (BITS == 2 || BITS == 3 || BITS == 4) {
+      const u32x4_t v = *reinterpret_cast<const u32x4_t*>(sec + 4 * l);
+      w[0] = v[0]; w[1] = v[1]; w[2] = v[2]; w[3] = v[3];
+    }
+    if constexpr (BITS == 4) {
+      const u32x4_t v = *reinterpret_cast<const u32x4_t*>(sec + 256 + 4 * l);
+      w[4] = v[0]; w[5] = v[1]; w[6] = v[2]; w[7] = v[3];
+    }
+    if constexpr (BITS == 1 || BITS == 3) {
+      const u32x2_t v = *reinterpret_cast<const u32x2_t*>(sec + (BITS == 3 ? 256 : 0) + 2 * l);
+      h[0] = v[0]; h[1] = v[1];
+    }
+  }
+  __device__ __forceinline__ float code(int j, int hh, int slot) const {
+    uint32_t c;
+    if constexpr (BITS == 4) {
+      c = (w[4 * (slot >> 2) + j] >> (16 * hh + 4 * (slot & 3))) & 15u;
+    } else if constexpr (BITS == 1) {
+      c = (h[j >> 1] >> (16 * hh + 8 * (j & 1) + 2 * (slot & 3) + (slot >> 2))) & 1u;
+    } else {
+      c = (w[j] >> (16 * hh + 2 * slot)) & 3u;
+      if constexpr (BITS == 3) c += 4u * ((h[j >> 1] >> (16 * hh + 8 * (j & 1) + 2 * (slot & 3) + (slot >> 2))) & 1u);
+    }
+    return (float)c;
+  }
+};
+
+// step of in-group element gi: the two 2-bit elements of a 3-bit group divide the same range by 3
+template <int BITS> __device__ __forceinline__ float step_of(float s, bool two_bit_elem) {
+  if (BITS == 3 && two_bit_elem) return (s * 7.0f) / 3.0f;
+  return s;
+}
+
+template <int KB, int VB>
 __global__ __launch_bounds__(kMixWaves * kWave) void mixed_fronts_kernel(MixedArgs a) {
-  __shared__ float X[kMixWaves][kTile][kPitch];   // one tile of Key rows, then of Value rows, as fp32
-  __shared__ float Q[kHeads][kD];
+  __shared__ __attribute__((aligned(16))) float X[kMixWaves][kTile][kPitch];   // one tile of Key rows, then of Value rows, as fp32;
+                                                                               // at the end the wave's result [head][channel]
+  __shared__ __attribute__((aligned(16))) float Q[kHeads][kD];
   __shared__ float P[kMixWaves][kHeads][kTile];   // softmax numerators of the tile
   __shared__ float Rm[kMixWaves][kHeads], Rl[kMixWaves][kHeads];
-  __shared__ float Ro[kMixWaves][kHeads][kD];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int u = blockIdx.x, uo = u * (int)gridDim.y + (int)blockIdx.y;   // (unit, head block): rows uo*G .. uo*G+G-1 of q
@@ -54,24 +96,82 @@ __global__ __launch_bounds__(kMixWaves * kWave) void mixed_fronts_kernel(MixedAr
 #pragma unroll
   for (int hh = 0; hh < kHeads; hh++) { m[hh] = -INFINITY; l[hh] = 0.0f; o0[hh] = 0.0f; o1[hh] = 0.0f; }
 
-  const size_t rec_words = (size_t)record_words(a.k_bits, a.v_bits);
-  // one tile of rows into the staging area: which = 0 Keys, 1 Values; rows of tokens at or past t_end are zero
+  float (&Xw)[kTile][kPitch] = X[wave];
+  const int kq = lane >> 4, i16 = lane & 15;
+
+  // ---- one tile of rows into the wave's staging area; rows of tokens at or past t_end become zero
+  // fp16 ring rows: 16-byte piece lane + 64*jj is token (lane + 64*jj) / 16, channels 8*(lane % 16) .. +7
+  // (only the rows of tokens from `first` on are written)
+  auto stage_ring = [&](const uint16_t* ring, int t0, int first) {
+#pragma unroll
+    for (int jj = 0; jj < 8; jj++) {
+      const int tau = 4 * jj + kq, t = t0 + tau;
+      if (t < first) continue;
+      float4_t lo = {0, 0, 0, 0}, hi = {0, 0, 0, 0};
+      if (t < a.t_end) {
+        const int slot = (a.slot_begin + (t - a.t_begin)) % a.W_cap;
+        const half8_t v = *reinterpret_cast<const half8_t*>(ring + ((size_t)u * a.W_cap + slot) * kD + 8 * i16);
+        lo = float4_t{(float)v[0], (float)v[1], (float)v[2], (float)v[3]};
+        hi = float4_t{(float)v[4], (float)v[5], (float)v[6], (float)v[7]};
+      }
+      *reinterpret_cast<float4_t*>(&Xw[tau][8 * i16]) = lo;
+      *reinterpret_cast<float4_t*>(&Xw[tau][8 * i16 + 4]) = hi;
+    }
+  };
+  // a packed Key tile: lane = column l holds channels 32*ks + 8*kq + 2*j + hh of tokens 8*(i/4) + 4*m + i%4 (slot = ks + 4*m)
+  auto stage_keys = [&](const uint32_t* rec) {
+    Column<KB> col;
+    col.load(rec + kMetaWords, lane);
+    const int tau_m[2] = {8 * (i16 >> 2) + (i16 & 3), 8 * (i16 >> 2) + 4 + (i16 & 3)};
+#pragma unroll
+    for (int ks = 0; ks < 4; ks++)
+#pragma unroll
+      for (int j = 0; j < 4; j++) {
+        const u32x2_t sm = *reinterpret_cast<const u32x2_t*>(rec + 4 * (16 * ks + 4 * kq + j));   // (scale pair, minimum pair) of channels d, d + 1
+#pragma unroll
+        for (int hh = 0; hh < 2; hh++) {
+          const float s = h2f(sm[0], hh), mn = h2f(sm[1], hh);
+          const int d = 32 * ks + 8 * kq + 2 * j + hh;
+#pragma unroll
+          for (int mm = 0; mm < 2; mm++) {
+            const int tau = tau_m[mm];
+            const float prod = col.code(j, hh, ks + 4 * mm) * step_of<KB>(s, tau == 10 || tau == 21);
+            Xw[tau][d] = prod + mn;
+          }
+        }
+      }
+  };
+  // a packed Value tile: lane = column l holds tokens 8*kq + 2*j + hh, channels 16*slot + i
+  auto stage_values = [&](const uint32_t* rec) {
+    Column<VB> col;
+    col.load(rec + kMetaWords + tile_words(KB), lane);
+#pragma unroll
+    for (int g = 0; g < 4; g++)
+#pragma unroll
+      for (int j = 0; j < 4; j++) {
+        const u32x2_t sm = *reinterpret_cast<const u32x2_t*>(rec + 4 * (16 * g + 4 * kq + j) + 2);   // groups (tau, g), (tau + 1, g)
+#pragma unroll
+        for (int hh = 0; hh < 2; hh++) {
+          const float s = h2f(sm[0], hh), mn = h2f(sm[1], hh);
+          const int tau = 8 * kq + 2 * j + hh;
+#pragma unroll
+          for (int sp = 0; sp < 2; sp++) {
+            const int gi = 16 * sp + i16;
+            const float prod = col.code(j, hh, 2 * g + sp) * step_of<VB>(s, gi == 10 || gi == 21);
+            Xw[tau][32 * g + gi] = prod + mn;
+          }
+        }
+      }
+  };
   auto stage = [&](int which, int t0) {
     const int front = which ? a.n_qv : a.n_qk;
     const uint16_t* ring = which ? a.v_win : a.k_win;
-    for (int e = lane; e < kTile * kD; e += kWave) {
-      const int tau = e / kD, d = e % kD, t = t0 + tau;
-      float x = 0.0f;
-      if (t < a.t_end) {
-        if (t < front) {
-          x = dequant_elem(a.packed + ((size_t)u * a.tiles_cap + t / kTile) * rec_words, a.k_bits, a.v_bits, which, tau, d);
-        } else {
-          const int slot = (a.slot_begin + (t - a.t_begin)) % a.W_cap;
-          x = (float)__builtin_bit_cast(half_t, ring[((size_t)u * a.W_cap + slot) * kD + d]);
-        }
-      }
-      X[wave][tau][d] = x;
-    }
+    const uint32_t* rec = a.packed + ((size_t)u * a.tiles_cap + t0 / kTile) * (size_t)record_words(KB, VB);
+    if (t0 >= front) { stage_ring(ring, t0, t0); return; }
+    if (which) stage_values(rec); else stage_keys(rec);
+    // A front inside the tile (Values only: the Key front is a multiple of 32): the rows from the front on are
+    // overwritten with the ring's (what the record holds for them is unspecified), rows past the end with zeros.
+    if (t0 + kTile > front) { wave_fence(); stage_ring(ring, t0, front); }
   };
 
   const int n_tiles = (a.t_end - a.t_begin + kTile - 1) / kTile;
@@ -81,13 +181,25 @@ __global__ __launch_bounds__(kMixWaves * kWave) void mixed_fronts_kernel(MixedAr
     stage(0, t0);
     wave_fence();
     const bool live = t0 + tau < a.t_end;
+    float s[kHeads];
+#pragma unroll
+    for (int hh = 0; hh < kHeads; hh++) s[hh] = 0.0f;
+#pragma unroll 4
+    for (int c = 0; c < 16; c++) {
+      const float4_t x = *reinterpret_cast<const float4_t*>(&Xw[tau][64 * part + 4 * c]);
+#pragma unroll
+      for (int hh = 0; hh < kHeads; hh++) {
+        if (hh < G) {
+          const float4_t qv = *reinterpret_cast<const float4_t*>(&Q[hh][64 * part + 4 * c]);
+          s[hh] += x[0] * qv[0] + x[1] * qv[1] + x[2] * qv[2] + x[3] * qv[3];
+        }
+      }
+    }
 #pragma unroll
     for (int hh = 0; hh < kHeads; hh++) {
       if (hh < G) {
-        float s = 0.0f;
-        for (int d = 0; d < kD / 2; d++) s += Q[hh][64 * part + d] * X[wave][tau][64 * part + d];
-        s += __shfl_xor(s, 32);
-        const float x = live ? s * a.scale_log2 : -INFINITY;
+        const float st = s[hh] + __shfl_xor(s[hh], 32);
+        const float x = live ? st * a.scale_log2 : -INFINITY;
         const float mnew = fmaxf(m[hh], wave_max_f(x));     // finite: every tile has at least one live token
         const float f = exp2f(m[hh] - mnew);                // 0 on the wave's first tile
         const float p = exp2f(x - mnew);                    // 0 for rows past the end
@@ -100,27 +212,28 @@ __global__ __launch_bounds__(kMixWaves * kWave) void mixed_fronts_kernel(MixedAr
     wave_fence();
     stage(1, t0);
     wave_fence();
+#pragma unroll 4
+    for (int t = 0; t < kTile; t++) {
+      const float x0 = Xw[t][lane], x1 = Xw[t][lane + kWave];
 #pragma unroll
-    for (int hh = 0; hh < kHeads; hh++) {
-      if (hh < G) {
-        float a0 = o0[hh], a1 = o1[hh];
-        for (int t = 0; t < kTile; t++) {
+      for (int hh = 0; hh < kHeads; hh++) {
+        if (hh < G) {
           const float p = P[wave][hh][t];
-          a0 += p * X[wave][t][lane];
-          a1 += p * X[wave][t][lane + kWave];
+          o0[hh] += p * x0;
+          o1[hh] += p * x1;
         }
-        o0[hh] = a0; o1[hh] = a1;
       }
     }
     wave_fence();
   }
 
+  // the wave's result into its own staging area (rows 0 .. G-1 hold [head][channel])
 #pragma unroll
   for (int hh = 0; hh < kHeads; hh++) {
     if (hh < G) {
       if (lane == 0) { Rm[wave][hh] = m[hh]; Rl[wave][hh] = l[hh]; }
-      Ro[wave][hh][lane] = o0[hh];
-      Ro[wave][hh][lane + kWave] = o1[hh];
+      Xw[hh][lane] = o0[hh];
+      Xw[hh][lane + kWave] = o1[hh];
     }
   }
   __syncthreads();
@@ -134,7 +247,7 @@ __global__ __launch_bounds__(kMixWaves * kWave) void mixed_fronts_kernel(MixedAr
     for (int w = 0; w < kMixWaves; w++) {
       const float f = Rm[w][hh] == -INFINITY ? 0.0f : exp2f(Rm[w][hh] - M);
       L += Rl[w][hh] * f;
-      O += Ro[w][hh][d] * f;
+      O += X[w][hh][d] * f;
     }
     float* pp = a.part + (((size_t)uo * a.n_parts + a.part_index) * G + hh) * (kD + 2);
     if (d == 0) { pp[0] = M; pp[1] = L; }
@@ -142,12 +255,36 @@ __global__ __launch_bounds__(kMixWaves * kWave) void mixed_fronts_kernel(MixedAr
   }
 }
 
+template <int KB, int VB>
+hipError_t launch_mx(const MixedArgs& a, dim3 grid, hipStream_t s) {
+  mixed_fronts_kernel<KB, VB><<<grid, kMixWaves * kWave, 0, s>>>(a);
+  return hipGetLastError();
+}
+
 }  // namespace
 
 hipError_t launch_mixed_fronts(const MixedArgs& a, int units, int head_blocks, hipStream_t s) {
   if (units == 0 || a.t_end <= a.t_begin) return hipSuccess;
-  mixed_fronts_kernel<<<dim3(units, head_blocks), kMixWaves * kWave, 0, s>>>(a);
-  return hipGetLastError();
+  const dim3 grid(units, head_blocks);
+  switch (a.k_bits * 10 + a.v_bits) {
+    case 11: return launch_mx<1, 1>(a, grid, s);
+    case 12: return launch_mx<1, 2>(a, grid, s);
+    case 13: return launch_mx<1, 3>(a, grid, s);
+    case 14: return launch_mx<1, 4>(a, grid, s);
+    case 21: return launch_mx<2, 1>(a, grid, s);
+    case 31: return launch_mx<3, 1>(a, grid, s);
+    case 41: return launch_mx<4, 1>(a, grid, s);
+    case 22: return launch_mx<2, 2>(a, grid, s);
+    case 23: return launch_mx<2, 3>(a, grid, s);
+    case 24: return launch_mx<2, 4>(a, grid, s);
+    case 32: return launch_mx<3, 2>(a, grid, s);
+    case 33: return launch_mx<3, 3>(a, grid, s);
+    case 34: return launch_mx<3, 4>(a, grid, s);
+    case 42: return launch_mx<4, 2>(a, grid, s);
+    case 43: return launch_mx<4, 3>(a, grid, s);
+    case 44: return launch_mx<4, 4>(a, grid, s);
+  }
+  return hipErrorInvalidValue;
 }
 
 }  // namespace kvmix

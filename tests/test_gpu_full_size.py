@@ -72,16 +72,16 @@ def test_full_size_fused_steps(name, kb, vb, layer, steps):
     n_q0 = T - 8 - n_w0
     shape, cfg = kv.Shape(B, Hq, Hkv), kv.LayerCfg(kb, vb, W)
     q, k, v = synth.gen_layer_torch("cuda", synth.BASE_SEED, layer, B, Hq, Hkv, n_q0 + n_w0 + steps)
-    gc = kv.LayerCache(shape, cfg, T + 64, W + 32)
+    gc = kv.LayerCache(shape, cfg, T + synth.GEN_ROOM, W + 32)
     kv.quantize_pack(shape, cfg, k[:, :, :n_q0], v[:, :, :n_q0], gc)
     gc.set_window(k[:, :, n_q0:n_q0 + n_w0], v[:, :, n_q0:n_q0 + n_w0])
-    ws = torch.zeros(kv.workspace_bytes(shape, T + 64), dtype=torch.uint8, device="cuda")
+    ws = torch.zeros(kv.workspace_bytes(shape, T + synth.GEN_ROOM), dtype=torch.uint8, device="cuda")
     units = np.random.default_rng(11).choice(B * Hkv, 3, replace=False)
     refs = []
     for u in units:
         b, j = divmod(int(u), Hkv)
         ku, vu = t16(k[b, j]).reshape(1, 1, -1, 128), t16(v[b, j]).reshape(1, 1, -1, 128)
-        rc = RefCache(1, G, 1, kb, vb, W, T + 64, W + 32)
+        rc = RefCache(1, G, 1, kb, vb, W, T + synth.GEN_ROOM, W + 32)
         assert rc.quantize_pack(ku[:, :, :n_q0], vu[:, :, :n_q0]) == 0
         rc.set_window(ku[:, :, n_q0:n_q0 + n_w0], vu[:, :, n_q0:n_q0 + n_w0])
         refs.append((b, j, ku, vu, rc))
@@ -102,7 +102,7 @@ def test_full_size_fused_steps(name, kb, vb, layer, steps):
                               tight_abs=2.5e-4)
     assert gc.n_q == n_q0 + 32     # the flush happened inside the run
     assert not ws[: 4 * shape.units].any()
-    tiles = (T + 64) // 32
+    tiles = (T + synth.GEN_ROOM) // 32
     records = gc.packed.view(torch.int32).view(B * Hkv, tiles, -1)
     for (b, j, ku, vu, rc), u in zip(refs, units):                                   # the flushed tile, bit for bit
         nt = rc.n_q // 32
