@@ -99,86 +99,116 @@ __global__ __launch_bounds__(kMixWaves * kWave) void mixed_fronts_kernel(MixedAr
   float (&Xw)[kTile][kPitch] = X[wave];
   const int kq = lane >> 4, i16 = lane & 15;
 
-  // ---- one tile of rows into the wave's staging area; rows of tokens at or past t_end become zero
-  // fp16 ring rows: 16-byte piece lane + 64*jj is token (lane + 64*jj) / 16, channels 8*(lane % 16) .. +7
-  // (only the rows of tokens from `first` on are written)
-  auto stage_ring = [&](const uint16_t* ring, int t0, int first) {
+  // ---- A tile's rows reach the staging area in two steps, request and conversion, so that the requests of the
+  // next rows are in flight while the rows in hand are worked on.
+  // fp16 ring rows: 16-byte piece lane + 64*jj is token (lane + 64*jj) / 16, channels 8*(lane % 16) .. +7.
+  struct RingRaw { half8_t v[8]; };
+  auto load_ring = [&](const uint16_t* ring, int t0, RingRaw& r) {
+    // a row past the end is read from the last live token's slot instead (any slot is valid memory)
+    const int s0 = (a.slot_begin + (t0 - a.t_begin)) % a.W_cap;
+#pragma unroll
+    for (int jj = 0; jj < 8; jj++) {
+      const int tau = 4 * jj + kq;
+      const int tc = t0 + tau < a.t_end ? tau : a.t_end - 1 - t0;
+      int slot = s0 + tc;
+      if (slot >= a.W_cap) slot -= a.W_cap;
+      r.v[jj] = *reinterpret_cast<const half8_t*>(ring + ((size_t)u * a.W_cap + slot) * kD + 8 * i16);
+    }
+  };
+  // rows of tokens from `first` on are written, rows at or past t_end as zeros
+  auto conv_ring = [&](const RingRaw& r, int t0, int first) {
 #pragma unroll
     for (int jj = 0; jj < 8; jj++) {
       const int tau = 4 * jj + kq, t = t0 + tau;
-      if (t < first) continue;
-      float4_t lo = {0, 0, 0, 0}, hi = {0, 0, 0, 0};
-      if (t < a.t_end) {
-        const int slot = (a.slot_begin + (t - a.t_begin)) % a.W_cap;
-        const half8_t v = *reinterpret_cast<const half8_t*>(ring + ((size_t)u * a.W_cap + slot) * kD + 8 * i16);
-        lo = float4_t{(float)v[0], (float)v[1], (float)v[2], (float)v[3]};
-        hi = float4_t{(float)v[4], (float)v[5], (float)v[6], (float)v[7]};
+      const bool live = t < a.t_end;
+      float4_t lo = float4_t{(float)r.v[jj][0], (float)r.v[jj][1], (float)r.v[jj][2], (float)r.v[jj][3]};
+      float4_t hi = float4_t{(float)r.v[jj][4], (float)r.v[jj][5], (float)r.v[jj][6], (float)r.v[jj][7]};
+      if (!live) { lo = float4_t{0, 0, 0, 0}; hi = lo; }
+      if (t >= first) {
+        *reinterpret_cast<float4_t*>(&Xw[tau][8 * i16]) = lo;
+        *reinterpret_cast<float4_t*>(&Xw[tau][8 * i16 + 4]) = hi;
       }
-      *reinterpret_cast<float4_t*>(&Xw[tau][8 * i16]) = lo;
-      *reinterpret_cast<float4_t*>(&Xw[tau][8 * i16 + 4]) = hi;
     }
   };
-  // a packed Key tile: lane = column l holds channels 32*ks + 8*kq + 2*j + hh of tokens 8*(i/4) + 4*m + i%4 (slot = ks + 4*m)
-  auto stage_keys = [&](const uint32_t* rec) {
-    Column<KB> col;
-    col.load(rec + kMetaWords, lane);
+  // a packed Key tile: lane = column l holds channels 32*ks + 8*kq + 2*j + hh of tokens 8*(i/4) + 4*m + i%4 (slot = ks + 4*m);
+  // sm[4*ks + j] = (scale pair, minimum pair) of channels d, d + 1
+  struct KeyRaw { Column<KB> col; u32x2_t sm[16]; };
+  auto load_keys = [&](const uint32_t* rec, KeyRaw& r) {
+    r.col.load(rec + kMetaWords, lane);
+#pragma unroll
+    for (int ks = 0; ks < 4; ks++)
+#pragma unroll
+      for (int j = 0; j < 4; j++) r.sm[4 * ks + j] = *reinterpret_cast<const u32x2_t*>(rec + 4 * (16 * ks + 4 * kq + j));
+  };
+  auto conv_keys = [&](const KeyRaw& r) {
     const int tau_m[2] = {8 * (i16 >> 2) + (i16 & 3), 8 * (i16 >> 2) + 4 + (i16 & 3)};
 #pragma unroll
     for (int ks = 0; ks < 4; ks++)
 #pragma unroll
-      for (int j = 0; j < 4; j++) {
-        const u32x2_t sm = *reinterpret_cast<const u32x2_t*>(rec + 4 * (16 * ks + 4 * kq + j));   // (scale pair, minimum pair) of channels d, d + 1
+      for (int j = 0; j < 4; j++)
 #pragma unroll
         for (int hh = 0; hh < 2; hh++) {
-          const float s = h2f(sm[0], hh), mn = h2f(sm[1], hh);
+          const float s = h2f(r.sm[4 * ks + j][0], hh), mn = h2f(r.sm[4 * ks + j][1], hh);
           const int d = 32 * ks + 8 * kq + 2 * j + hh;
 #pragma unroll
           for (int mm = 0; mm < 2; mm++) {
             const int tau = tau_m[mm];
-            const float prod = col.code(j, hh, ks + 4 * mm) * step_of<KB>(s, tau == 10 || tau == 21);
+            const float prod = r.col.code(j, hh, ks + 4 * mm) * step_of<KB>(s, tau == 10 || tau == 21);
             Xw[tau][d] = prod + mn;
           }
         }
-      }
   };
-  // a packed Value tile: lane = column l holds tokens 8*kq + 2*j + hh, channels 16*slot + i
-  auto stage_values = [&](const uint32_t* rec) {
-    Column<VB> col;
-    col.load(rec + kMetaWords + tile_words(KB), lane);
+  // a packed Value tile: lane = column l holds tokens 8*kq + 2*j + hh, channels 16*slot + i;
+  // sm[4*g + j] = (scale pair, minimum pair) of the groups (tau, g), (tau + 1, g)
+  struct ValueRaw { Column<VB> col; u32x2_t sm[16]; };
+  auto load_values = [&](const uint32_t* rec, ValueRaw& r) {
+    r.col.load(rec + kMetaWords + tile_words(KB), lane);
 #pragma unroll
     for (int g = 0; g < 4; g++)
 #pragma unroll
-      for (int j = 0; j < 4; j++) {
-        const u32x2_t sm = *reinterpret_cast<const u32x2_t*>(rec + 4 * (16 * g + 4 * kq + j) + 2);   // groups (tau, g), (tau + 1, g)
+      for (int j = 0; j < 4; j++) r.sm[4 * g + j] = *reinterpret_cast<const u32x2_t*>(rec + 4 * (16 * g + 4 * kq + j) + 2);
+  };
+  auto conv_values = [&](const ValueRaw& r) {
+#pragma unroll
+    for (int g = 0; g < 4; g++)
+#pragma unroll
+      for (int j = 0; j < 4; j++)
 #pragma unroll
         for (int hh = 0; hh < 2; hh++) {
-          const float s = h2f(sm[0], hh), mn = h2f(sm[1], hh);
+          const float s = h2f(r.sm[4 * g + j][0], hh), mn = h2f(r.sm[4 * g + j][1], hh);
           const int tau = 8 * kq + 2 * j + hh;
 #pragma unroll
           for (int sp = 0; sp < 2; sp++) {
             const int gi = 16 * sp + i16;
-            const float prod = col.code(j, hh, 2 * g + sp) * step_of<VB>(s, gi == 10 || gi == 21);
+            const float prod = r.col.code(j, hh, 2 * g + sp) * step_of<VB>(s, gi == 10 || gi == 21);
             Xw[tau][32 * g + gi] = prod + mn;
           }
         }
-      }
   };
-  auto stage = [&](int which, int t0) {
-    const int front = which ? a.n_qv : a.n_qk;
-    const uint16_t* ring = which ? a.v_win : a.k_win;
-    const uint32_t* rec = a.packed + ((size_t)u * a.tiles_cap + t0 / kTile) * (size_t)record_words(KB, VB);
-    if (t0 >= front) { stage_ring(ring, t0, t0); return; }
-    if (which) stage_values(rec); else stage_keys(rec);
-    // A front inside the tile (Values only: the Key front is a multiple of 32): the rows from the front on are
-    // overwritten with the ring's (what the record holds for them is unspecified), rows past the end with zeros.
-    if (t0 + kTile > front) { wave_fence(); stage_ring(ring, t0, front); }
+  // Where a tile's rows live (wave-uniform). Keys: packed before the Key front (a multiple of 32), else the ring.
+  // Values: packed, ring, or - the tile in which the Value front stands - the record's rows up to the front and the
+  // ring's from it on (what the record holds for those is unspecified).
+  auto rec_of = [&](int t0) { return a.packed + ((size_t)u * a.tiles_cap + t0 / kTile) * (size_t)record_words(KB, VB); };
+  auto keys_packed = [&](int t0) { return t0 < a.n_qk; };
+  auto values_from_record = [&](int t0) { return t0 < a.n_qv; };
+  auto values_from_ring = [&](int t0) { return t0 + kTile > a.n_qv; };
+  RingRaw kr, vr;
+  KeyRaw kp;
+  ValueRaw vp;
+  auto request_keys = [&](int t0) { if (keys_packed(t0)) load_keys(rec_of(t0), kp); else load_ring(a.k_win, t0, kr); };
+  auto request_values = [&](int t0) {
+    if (values_from_record(t0)) load_values(rec_of(t0), vp);
+    if (values_from_ring(t0)) load_ring(a.v_win, t0, vr);
   };
 
   const int n_tiles = (a.t_end - a.t_begin + kTile - 1) / kTile;
   const int tau = lane & 31, part = lane >> 5;   // scores: lane (tau, part) sums channels 64*part .. 64*part + 63 of token tau
+  if (wave < n_tiles) { request_keys(a.t_begin + wave * kTile); request_values(a.t_begin + wave * kTile); }
   for (int jt = wave; jt < n_tiles; jt += kMixWaves) {
-    const int t0 = a.t_begin + jt * kTile;
-    stage(0, t0);
+    const int t0 = a.t_begin + jt * kTile, t_next = t0 + kMixWaves * kTile;
+    const bool more = jt + kMixWaves < n_tiles;
+    if (keys_packed(t0)) conv_keys(kp); else conv_ring(kr, t0, t0);
+    if (more) request_keys(t_next);          // the Key registers are free again: the next tile's rows travel during the rest
     wave_fence();
     const bool live = t0 + tau < a.t_end;
     float s[kHeads];
@@ -210,7 +240,12 @@ __global__ __launch_bounds__(kMixWaves * kWave) void mixed_fronts_kernel(MixedAr
       }
     }
     wave_fence();
-    stage(1, t0);
+    if (values_from_record(t0)) conv_values(vp);
+    if (values_from_ring(t0)) {
+      if (values_from_record(t0)) wave_fence();
+      conv_ring(vr, t0, a.n_qv > t0 ? a.n_qv : t0);
+    }
+    if (more) request_values(t_next);
     wave_fence();
 #pragma unroll 4
     for (int t = 0; t < kTile; t++) {
