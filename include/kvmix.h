@@ -62,9 +62,8 @@
  * Recent window (fp16, ring buffer of W_cap slots, W_cap % 32 == 0, W_cap >= window + 32)
  *   k_win, v_win : [units][W_cap][128]   (channel contiguous: appending a token writes one full row of each)
  *   The sequence has n = n_q + n_w tokens; token t >= n_q sits in slot (w0 + t - n_q) % W_cap of both windows, so
- *   the n_w window tokens are slots (w0 + r) % W_cap, r = 0..n_w-1, oldest first; w0 % 32 == 0. Both windows must
- *   hold finite values in every slot (zero-fill at allocation): slots outside the valid ones are masked by
- *   multiplying with zero, not skipped.
+ *   the n_w window tokens are slots (w0 + r) % W_cap, r = 0..n_w-1, oldest first; w0 % 32 == 0. Slots outside the
+ *   live tokens are never read (they may hold anything, NaN patterns included).
  *   Keys and Values may age at fronts of their own (Sec. 3.3: the ratio of a layer's Keys and Values may differ):
  *   Keys of tokens [0, n_q) are packed, Values of tokens [0, n_q + v_lead). A Key group runs along 32 tokens, so
  *   the Key front n_q is a multiple of 32; a Value group is one token's 32 channels, so the Value front may stand

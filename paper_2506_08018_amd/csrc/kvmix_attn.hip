@@ -374,7 +374,10 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
 #pragma unroll
     for (int m = 0; m < 2; m++) {
       const int tau = 8 * (col >> 2) + 4 * m + (col & 3);   // row `col` of M-tile m
-      const uint16_t* rowp = (has_new && tau == new_tau) ? kn : kw + (size_t)tau * kD;
+      // a slot past the live tokens is not read: its lanes take the tile's first row instead (live, and already on its
+      // way: a cache hit), whose products the softmax mask discards; no byte of a dead slot reaches the arithmetic
+      const int tau_r = win_first(wi) + tau < a.n_w ? tau : 0;
+      const uint16_t* rowp = (has_new && tau == new_tau) ? kn : kw + (size_t)tau_r * kD;
 #pragma unroll
       for (int ks = 0; ks < 4; ks++) w.Ak[m][ks] = *reinterpret_cast<const half8_t*>(rowp + 32 * ks + 8 * kq);
     }
@@ -388,7 +391,8 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
     const bool has_new = wi == new_tile;
 #pragma unroll
     for (int j = 0; j < 8; j++) {
-      const uint16_t* rowp = (has_new && 4 * j + kq == new_tau) ? vn : vw + (size_t)(4 * j + kq) * kD;
+      const int tv = win_first(wi) + 4 * j + kq < a.n_w ? 4 * j + kq : 0;      // dead slots: the first row again (weight zero)
+      const uint16_t* rowp = (has_new && 4 * j + kq == new_tau) ? vn : vw + (size_t)tv * kD;
       w.Vr[j] = *reinterpret_cast<const u32x4_t*>(rowp + 8 * col);
     }
   };

@@ -116,8 +116,10 @@ def test_sharp_softmax_and_large_values():
 
 @pytest.mark.parametrize("G,kb,vb", [(1, 2, 2), (4, 3, 4), (8, 2, 3)])
 def test_stale_ring_slots_and_key_outliers(G, kb, vb):
-    """(a) Ring slots outside the live window hold large finite leftovers (not zeros): they are masked, the result
-    does not change. (b) Key channel outliers of x100 (group scales in the hundreds, folded into fp16 operands)."""
+    """(a) Ring slots outside the live window hold leftovers: NaN patterns in the Key ring, infinities and large
+    values in the Value ring. Dead slots are never read, the result does not change, also through fused steps whose
+    new token lands on such a slot. (b) Key channel outliers of x100 (group scales in the hundreds, folded into
+    fp16 operands)."""
     import torch
     print(f"case stale slots / outliers G={G} kb={kb} vb={vb}", flush=True)
     B, Hkv, T, W = 1, 2, 32 * 14 + 9, 32
@@ -126,14 +128,26 @@ def test_stale_ring_slots_and_key_outliers(G, kb, vb):
     k[:, 1, :, 77] *= 100.0
     _, _, _, rc, gc, shape, cfg = make_pair(B, Hkv * G, Hkv, T, W, kb, vb, W_cap=128, q_k_v=(q, k, v))
     assert gc.n_w == 41 and gc.W_cap == 128
-    junk_k = torch.full((shape.units, 128 - 41, 128), 6.0e4, dtype=torch.float16, device="cuda")
+    junk_k = torch.full((shape.units, 128 - 41, 128), float("nan"), dtype=torch.float16, device="cuda")
     junk_v = torch.full((shape.units, 128 - 41, 128), -6.0e4, dtype=torch.float16, device="cuda")
+    junk_v[:, ::3] = float("inf")
     gc.k_win.view(torch.float16).view(shape.units, 128, 128)[:, 41:] = junk_k
     gc.v_win.view(torch.float16).view(shape.units, 128, 128)[:, 41:] = junk_v
     st, want = rc.decode_attn(u16(q))
     assert st == 0
     for ns in (1, 2):
         assert_attn_close(run_attn(gc, shape, cfg, q, n_splits=ns), want, f"stale slots G={G} splits={ns}")
+    import paper_2506_08018_amd as kv
+    kn, vn = synth.gen_layer_numpy(721, 1, B, Hkv, Hkv, 3)[1:]
+    qt = torch.from_numpy(q).cuda()
+    out = torch.zeros_like(qt)
+    ws = torch.zeros(kv.workspace_bytes(shape, gc.T_cap), dtype=torch.uint8, device="cuda")
+    for s_ in range(3):
+        assert rc.append(u16(kn[:, :, s_]), u16(vn[:, :, s_])) == 0
+        st, want = rc.decode_attn(u16(q))
+        kv.decode_step(shape, cfg, torch.from_numpy(kn[:, :, s_].copy()).cuda(), torch.from_numpy(vn[:, :, s_].copy()).cuda(), qt, gc, out, ws)
+        torch.cuda.synchronize()
+        assert_attn_close(t16(out), want, f"stale slots G={G} fused step {s_}")
 
 
 @pytest.mark.parametrize("kb,vb,G", [(2, 2, 1), (3, 4, 4)])
