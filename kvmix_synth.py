@@ -16,7 +16,7 @@ GEN_ROOM = 320
 OUTLIER_CHANNELS = 4
 OUTLIER_GAIN = 10.0
 
-# The five workloads of the benchmark spec (T = context including the token being decoded).
+# The five benchmark workloads (T = context including the token being decoded).
 CONFIGS = {
     "cfg1_single_layer": dict(L=1, B=1, Hq=32, Hkv=32, T=1024, W=32, bits="2/2"),
     "cfg2_llama2_7b": dict(L=32, B=8, Hq=32, Hkv=32, T=4096, W=128, bits="table"),

@@ -299,7 +299,7 @@ def test_many_tiles_per_wave(kb, vb, G):
 
 
 def test_config1_full_parity():
-    """BASELINE config 1 in full: 1 layer, B1, 32 heads, T1024, window 32, K2/V2."""
+    """Benchmark configuration 1 in full: 1 layer, B1, 32 heads, T1024, window 32, K2/V2."""
     print("case config1", flush=True)
     c = synth.CONFIGS["cfg1_single_layer"]
     q, k, v, rc, gc, shape, cfg = make_pair(c["B"], c["Hq"], c["Hkv"], c["T"], c["W"], 2, 2, seed=synth.BASE_SEED)
