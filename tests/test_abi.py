@@ -166,3 +166,58 @@ def test_append_tokens_checks_capacity_for_the_whole_call(kv):
     cfg16 = kv.LayerCfg(16, 16, 0)
     assert L.kvmix_append_tokens(C.byref(sh), C.byref(cfg16), a, a, 128, 128, 512, 5, C.byref(c16), None) == -4
     assert c16.n_w == 60
+
+
+def test_rpc_next_is_host_arithmetic_and_matches_the_oracle(kv):
+    """kvmix_rpc_next needs no GPU: floor(r * current) per side (Sec. 3.3), against the oracle's formula and the
+    sequence worked by hand from a 1024-token prompt (r = 0.2 for Keys, 0.1 for Values: Sec. 4.2)."""
+    from oracle import kvmix_ref as ref
+    assert kv.rpc_next(0.2, 0.1, 1024, 1024) == (204, 102)
+    kept_k, kept_v, seq = 204, 102, []
+    for _ in range(4):
+        kept_k, kept_v = kv.rpc_next(0.2, 0.1, kept_k + 1, kept_v + 1)
+        seq.append((kept_k, kept_v))
+    assert seq == [(41, 10), (8, 1), (1, 0), (0, 0)]
+    for r in (0.0, 0.05, 0.1, 0.2, 0.3, 1.0):
+        for cur in (0, 1, 9, 10, 11, 99, 1000, 4095, 32768):
+            assert kv.rpc_next(r, r, cur, cur) == (ref.rpc_next(r, cur),) * 2
+    import ctypes as C
+    L = kv.lib()
+    n = C.c_int(7)
+    assert L.kvmix_rpc_next(0.2, 0.1, 5, 5, None, C.byref(n)) == -1
+    assert L.kvmix_rpc_next(-0.1, 0.1, 5, 5, C.byref(n), C.byref(n)) == -4
+    assert L.kvmix_rpc_next(0.2, 1.5, 5, 5, C.byref(n), C.byref(n)) == -4
+    assert L.kvmix_rpc_next(0.2, 0.1, -1, 5, C.byref(n), C.byref(n)) == -4
+    assert L.kvmix_rpc_next(float("nan"), 0.1, 5, 5, C.byref(n), C.byref(n)) == -4
+    assert n.value == 7
+
+
+def test_flush_and_fronts_are_checked_on_the_host(kv):
+    """kvmix_flush and the calls that take a cache with fronts apart reject bad states before anything is launched."""
+    import ctypes as C
+    from paper_2506_08018_amd.binding import _CacheStruct
+    L = kv.lib()
+    sh, ring, fixed = kv.Shape(1, 4, 4), kv.LayerCfg(2, 2, -1), kv.LayerCfg(2, 2, 32)
+    a = C.c_void_p(4096)
+    c = _CacheStruct(4096, 4096, 4096, 64, 64, 32, 20, 32, 0)
+    assert L.kvmix_flush(C.byref(sh), C.byref(ring), C.byref(c), -1, 0, None) == -4
+    assert L.kvmix_flush(C.byref(sh), C.byref(ring), None, 0, 0, None) == -1
+    assert L.kvmix_flush(C.byref(sh), C.byref(kv.LayerCfg(16, 16, 0)), C.byref(c), 0, 0, None) == -2
+    assert L.kvmix_flush(C.byref(sh), C.byref(kv.LayerCfg(2, 2, -2)), C.byref(c), 0, 0, None) == -4        # window: -1 or a multiple of 32
+    assert L.kvmix_flush(C.byref(sh), C.byref(ring), C.byref(c), 100, 100, None) == 0                      # nothing has to leave: no launch
+    assert (c.n_q, c.n_w, c.w0, c.v_lead) == (32, 20, 32, 0)
+    over = _CacheStruct(4096, 4096, 4096, 32, 64, 32, 40, 32, 0)                                            # T_cap 32: no room for any front to move
+    assert L.kvmix_flush(C.byref(sh), C.byref(ring), C.byref(over), 0, 0, None) == -4
+    assert (over.n_q, over.n_w, over.v_lead) == (32, 40, 0)
+    for bad_lead in (21, -33):          # Value front beyond the newest token / before token 0
+        bad = _CacheStruct(4096, 4096, 4096, 64, 64, 32, 20, 32, bad_lead)
+        assert L.kvmix_flush(C.byref(sh), C.byref(ring), C.byref(bad), 0, 0, None) == -4
+        assert L.kvmix_decode_attn(C.byref(sh), C.byref(ring), a, C.byref(bad), C.c_float(0.0), a, a, 1 << 20, 1, None) == -4
+    apart = _CacheStruct(4096, 4096, 4096, 64, 64, 32, 20, 32, 7)
+    # fixed-window ageing needs both fronts together
+    assert L.kvmix_append(C.byref(sh), C.byref(fixed), a, a, C.byref(apart), None) == -4
+    assert L.kvmix_decode_step(C.byref(sh), C.byref(fixed), a, a, a, C.byref(apart), C.c_float(0.0), a, a, 1 << 20, 1, None) == -4
+    # fronts apart: the extra partial needs the workspace even with one split
+    assert L.kvmix_decode_attn(C.byref(sh), C.byref(ring), a, C.byref(apart), C.c_float(0.0), a, None, 0, 1, None) == -1
+    assert L.kvmix_decode_attn(C.byref(sh), C.byref(ring), a, C.byref(apart), C.c_float(0.0), a, a, 64, 1, None) == -6
+    assert (apart.n_q, apart.n_w, apart.w0, apart.v_lead) == (32, 20, 32, 7)
