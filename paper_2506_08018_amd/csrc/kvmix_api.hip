@@ -342,7 +342,7 @@ int plan_attention(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const uint
     m.n_qk = c->n_q; m.n_qv = c->n_q + c->v_lead;
     m.t_begin = fr.packed_tiles * kTile; m.t_end = (int)fr.t_a;
     m.slot_begin = slot_of(c, m.t_begin);
-    m.G = G > 8 ? 8 : G;
+    m.G = G; m.G_main = G > 8 ? 8 : G;
     m.scale_log2 = a.scale_log2;
     plan->m = m;
   }
@@ -351,7 +351,7 @@ int plan_attention(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const uint
 
 int launch_plan(const AttnPlan& p, void* stream) {
   if (p.mixed) {
-    const hipError_t e = launch_mixed_fronts(p.m, p.units, p.G > 8 ? p.G / 8 : 1, (hipStream_t)stream);
+    const hipError_t e = launch_mixed_fronts(p.m, p.units, (hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(e);
   }
   const hipError_t e = launch_decode_attn(p.a, p.kb, p.vb, p.G, p.units, (hipStream_t)stream);

@@ -149,7 +149,7 @@ struct MixedArgs {
   int n_qk, n_qv;          // the two fronts
   int t_begin, t_end;      // t_begin is a multiple of 32
   int slot_begin;          // ring slot of token t_begin
-  int G;                   // heads per workgroup (at most 8)
+  int G, G_main;           // query heads per kv head; heads per (unit, block) pair of the main kernel's partials (min(G, 8))
   float scale_log2;
 };
 
@@ -157,7 +157,7 @@ hipError_t launch_quantize_pack(const QuantArgs& a, int k_bits, int v_bits,
                                 int n_tiles, int units, hipStream_t s);
 hipError_t launch_quantize_fronts(const QuantArgs& a, int k_bits, int v_bits,
                                   int n_tiles, int units, hipStream_t s);
-hipError_t launch_mixed_fronts(const MixedArgs& a, int units, int head_blocks, hipStream_t s);
+hipError_t launch_mixed_fronts(const MixedArgs& a, int units, hipStream_t s);
 hipError_t launch_dequant(const DequantArgs& a, int units, hipStream_t s);
 hipError_t launch_append(const AppendArgs& a, hipStream_t s);
 hipError_t launch_stream_read(const void* buf, size_t bytes, int workgroups, int threads, uint32_t* sink, hipStream_t s);
