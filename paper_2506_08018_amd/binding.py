@@ -40,6 +40,10 @@ def lib():
         if not os.path.exists(_LIB_PATH):
             raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_2506_08018_amd.build` "
                               "(there is no CPU fallback)")
+        # PyTorch first: it brings its own copy of the HIP runtime, and the buffers handed to this library are torch's.
+        # Loaded the other way round, the library binds to another copy of the runtime, to which torch's pointers
+        # mean nothing (every launch then fails with a HIP error).
+        import torch  # noqa: F401
         L = C.CDLL(_LIB_PATH)
         P, I, I64, SZ = C.c_void_p, C.c_int, C.c_int64, C.c_size_t
         L.kvmix_version.restype = I
