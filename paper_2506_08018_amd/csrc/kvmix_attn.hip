@@ -967,35 +967,36 @@ __global__ __launch_bounds__(waves_for(G) * kWave) void decode_attn_kernel(AttnA
   __syncthreads();
   if (!s_done) return;
   for (int idx = tid; idx < G * kD; idx += kThreads) {
-    const int hh = idx / kD, d = idx % kD;
+    const int hh = __builtin_amdgcn_readfirstlane(idx / kD), d = idx % kD;   // a wave's 64 outputs share the head
     const float* base = a.part + ((size_t)uo * a.n_parts * G + hh) * (kD + 2);
     const size_t stride = (size_t)G * (kD + 2);
-    // one pass, kMergeBatch splits per round trip: the loads of a batch are issued together
+    // one pass, kMergeBatch partials per round trip: lane k requests reference and sum of the batch's k-th
+    // partial, every lane its channel of each of them, all before the first use; the weights 2^(m_k - M) are
+    // computed once per wave (lane k holds the k-th) and handed out as scalars
     float M = -INFINITY, Lsum = 0.0f, O = 0.0f;
     for (int s0 = 0; s0 < a.n_parts; s0 += kMergeBatch) {
-      float ms[kMergeBatch], ls[kMergeBatch], os[kMergeBatch];
+      float mk = -INFINITY, lk = 0.0f;
+      if (lane < kMergeBatch && s0 + lane < a.n_parts) {
+        const float* pp = base + (size_t)(s0 + lane) * stride;
+        mk = ld_agent(pp);
+        lk = ld_agent(pp + 1);
+      }
+      float os[kMergeBatch];
 #pragma unroll
       for (int k = 0; k < kMergeBatch; k++) {
-        ms[k] = -INFINITY; ls[k] = 0.0f; os[k] = 0.0f;
-        if (s0 + k < a.n_parts) {           // wave-uniform: no request for partials that do not exist
-          const float* pp = base + (size_t)(s0 + k) * stride;
-          ms[k] = ld_agent(pp);
-          ls[k] = ld_agent(pp + 1);
-          os[k] = ld_agent(pp + 2 + d);
-        }
+        os[k] = 0.0f;
+        if (s0 + k < a.n_parts) os[k] = ld_agent(base + (size_t)(s0 + k) * stride + 2 + d);   // wave-uniform test
       }
-      float Mn = M;
-#pragma unroll
-      for (int k = 0; k < kMergeBatch; k++) Mn = fmaxf(Mn, ms[k]);
+      // cross-lane reads stay outside divergent code
+      const float mrow = row_max(mk);
+      const float Mn = fmaxf(M, fmaxf(uniform_lane(mrow, 0), uniform_lane(mrow, 16)));
       const float fold = (M == -INFINITY) ? 0.0f : fast_exp2(M - Mn);
-      Lsum *= fold;
+      const float fk = (mk == -INFINITY) ? 0.0f : fast_exp2(mk - Mn);
+      const float lrow = row_sum(lk * fk);
+      Lsum = Lsum * fold + (uniform_lane(lrow, 0) + uniform_lane(lrow, 16));
       O *= fold;
 #pragma unroll
-      for (int k = 0; k < kMergeBatch; k++) {
-        const float f = (ms[k] == -INFINITY) ? 0.0f : fast_exp2(ms[k] - Mn);
-        Lsum += ls[k] * f;
-        O += os[k] * f;
-      }
+      for (int k = 0; k < kMergeBatch; k++) O += os[k] * uniform_lane(fk, k);
       M = Mn;
     }
     outp[idx] = __builtin_bit_cast(uint16_t, (half_t)(O / Lsum));
