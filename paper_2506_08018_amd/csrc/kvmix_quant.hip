@@ -28,8 +28,14 @@ __device__ __forceinline__ int qmax_of(int i) {
 __device__ __forceinline__ uint32_t quad_x1(uint32_t v) { return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xf, 0xf, false); }
 __device__ __forceinline__ uint32_t quad_x2(uint32_t v) { return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xf, 0xf, false); }
 
-// Scale, minimum and the two reciprocal steps of one group from its extremes (fp32 images of fp16 values).
-struct GroupParams { float mn, s, inv, inv2; uint16_t scale_h, zero_h; };
+// Codes travel as "biased codes": the bit pattern of the float 1.5 * 2^23 + code, i.e. kBias + code. Adding
+// 1.5 * 2^23 to a value in [0, 2^22) rounds it to an integer (ties to even) in one operation and leaves that
+// integer in the low mantissa bits; the low 16 bits of kBias are zero.
+constexpr float kMagic = 12582912.0f;
+constexpr uint32_t kBias = 0x4B400000u;
+
+// Scale, minimum and bracketing reciprocal steps of one group from its extremes (fp32 images of fp16 values).
+struct GroupParams { float mn, s, inv_lo, inv_hi, inv2_lo, inv2_hi; bool slow; uint16_t scale_h, zero_h; };
 template <int BITS>
 __device__ __forceinline__ GroupParams group_params(float mn, float mx) {
   GroupParams g;
@@ -43,35 +49,45 @@ __device__ __forceinline__ GroupParams group_params(float mn, float mx) {
   g.s = (float)sh;
   g.scale_h = __builtin_bit_cast(uint16_t, sh);
   g.zero_h = __builtin_bit_cast(uint16_t, (half_t)mn);
-  // reciprocal steps (0 for a zero scale: every product, hence every code, is then 0)
-  g.inv = g.s != 0.0f ? 1.0f / g.s : 0.0f;
-  g.inv2 = g.s != 0.0f ? 1.0f / step_of<BITS>(g.s, 10) : 0.0f;   // the step of the two 2-bit elements of a 3-bit group
+  // 1 / s_i bracketed from below and above by 2^-19 relative: far more than the errors of the hardware
+  // reciprocal (1 ulp), of the products below and of the fp32 rounding of the true quotient taken together
+  // (under 2^-21). 0 for a zero scale: every product, hence every code, is then 0.
+  const float inv = g.s != 0.0f ? __builtin_amdgcn_rcpf(g.s) : 0.0f;
+  g.inv_lo = inv * (1.0f - 0x1p-19f);
+  g.inv_hi = inv * (1.0f + 0x1p-19f);
+  g.inv2_lo = g.inv_lo * (3.0f / 7.0f);          // the step s * 7 / 3 of the two 2-bit elements of a 3-bit group
+  g.inv2_hi = g.inv_hi * (3.0f / 7.0f);
+  // Only when the stored scale is a rounded image of range / q_max to fp16's full precision is every quotient
+  // at most q_max * (1 + 2^-11) and the upper clip idle. A subnormal scale (rounded with a larger relative error)
+  // or a saturated 1-bit scale sends the whole group down the exact path, which clips.
+  g.slow = (g.s != 0.0f && g.s < 0x1p-14f) || (BITS == 1 && g.s >= 65504.0f);
   return g;
 }
 
-// code = clamp(rint((x - mn) / s_i)) with the IEEE quotient. The quotient itself is only needed when it lies
-// next to a rounding boundary: (x - mn) * (1 / s_i) is within 3 * 2^-24 relative of it (quotients stay below
-// 16, i.e. within 3e-6 absolute), so whenever that product is farther than 1e-5 from k + 1/2 both round to the
-// same integer. quantize_fast reports the near cases; the caller redoes a small batch of elements with
-// quantize_exact when any of them was near (rare). x >= mn always, so only the upper clip can act.
-// i: index of the element inside its group.
+// code = clamp(rint((x - mn) / s_i)) with the IEEE quotient rounded to fp32 first. The quotient q lies strictly
+// between (x - mn) * inv_lo and (x - mn) * inv_hi, and so does its fp32 image; rounding to an integer is
+// monotone, so when both products round to the same integer (each with the single rounding of a fused
+// multiply-add onto kMagic), that integer is the code. quantize_fast reports the other cases - the quotient
+// within 2^-18 relative of k + 1/2, rare - and the caller redoes a small batch of elements with
+// quantize_exact when any of them was one. x >= mn always, and only the exact path needs the upper clip.
+// d: x - mn in fp32; i: index of the element inside its group. Both return biased codes.
 template <int BITS>
-__device__ __forceinline__ float quantize_fast(float x, const GroupParams& g, int i, bool& near) {
+__device__ __forceinline__ uint32_t quantize_fast(float d, const GroupParams& g, int i, bool& near) {
   const bool two_bit = BITS == 3 && (i == 10 || i == 21);
-  const float t = (x - g.mn) * (two_bit ? g.inv2 : g.inv);
-  const float r = __builtin_rintf(t);
-  near |= __builtin_fabsf(t - r) > 0.49999f;
-  return fminf(r, (float)qmax_of<BITS>(i));
+  const float lo = __builtin_fmaf(d, two_bit ? g.inv2_lo : g.inv_lo, kMagic);
+  const float hi = __builtin_fmaf(d, two_bit ? g.inv2_hi : g.inv_hi, kMagic);
+  near |= lo != hi;
+  return __builtin_bit_cast(uint32_t, lo);
 }
 template <int BITS>
-__device__ __forceinline__ float quantize_exact(float x, const GroupParams& g, int i) {
-  if (g.s == 0.0f) return 0.0f;
-  const float r = __builtin_rintf((x - g.mn) / step_of<BITS>(g.s, i));
-  return fminf(fmaxf(r, 0.0f), (float)qmax_of<BITS>(i));
+__device__ __forceinline__ uint32_t quantize_exact(float d, const GroupParams& g, int i) {
+  if (g.s == 0.0f) return kBias;
+  const float r = __builtin_rintf(d / step_of<BITS>(g.s, i));
+  return kBias + (uint32_t)fminf(fmaxf(r, 0.0f), (float)qmax_of<BITS>(i));
 }
+// x - mn in fp32 for an fp16 x: one fused operation (x * 1 - mn), rounded once like the subtraction
+__device__ __forceinline__ float diff(half_t x, float mn) { return __builtin_fmaf((float)x, 1.0f, -mn); }
 
-__device__ __forceinline__ float half_lo(uint32_t w) { return (float)__builtin_bit_cast(half_t, (uint16_t)(w & 0xffffu)); }
-__device__ __forceinline__ float half_hi(uint32_t w) { return (float)__builtin_bit_cast(half_t, (uint16_t)(w >> 16)); }
 __device__ __forceinline__ half2_t as_half2(uint32_t w) { return __builtin_bit_cast(half2_t, w); }
 
 // Number of 32-bit word accumulators a lane fills for one code section before the lanes of its quad are
@@ -187,33 +203,36 @@ __global__ __launch_bounds__(128) void quantize_pack_kernel(QuantArgs a) {
     for (int i = 0; i < acc_words<KB>(); i++) w[i] = 0;
 #pragma unroll
     for (int t0 = 0; t0 < kTile; t0 += 4) {
-      float r0[4], r1[4];
-      bool near = false;
+      uint32_t b0[4], b1[4];                         // biased codes of the lane's two channels
+      bool near = g0.slow || g1.slow;
 #pragma unroll
       for (int n = 0; n < 4; n++) {
-        r0[n] = quantize_fast<KB>(half_lo(xw[t0 + n]), g0, t0 + n, near);
-        r1[n] = quantize_fast<KB>(half_hi(xw[t0 + n]), g1, t0 + n, near);
+        const half2_t xv = as_half2(xw[t0 + n]);
+        b0[n] = quantize_fast<KB>(diff(xv[0], g0.mn), g0, t0 + n, near);
+        b1[n] = quantize_fast<KB>(diff(xv[1], g1.mn), g1, t0 + n, near);
       }
       if (near) {
 #pragma unroll
         for (int n = 0; n < 4; n++) {
-          r0[n] = quantize_exact<KB>(half_lo(xw[t0 + n]), g0, t0 + n);
-          r1[n] = quantize_exact<KB>(half_hi(xw[t0 + n]), g1, t0 + n);
+          const half2_t xv = as_half2(xw[t0 + n]);
+          b0[n] = quantize_exact<KB>(diff(xv[0], g0.mn), g0, t0 + n);
+          b1[n] = quantize_exact<KB>(diff(xv[1], g1.mn), g1, t0 + n);
         }
       }
 #pragma unroll
       for (int n = 0; n < 4; n++) {
-      const int t = t0 + n;
-      const uint32_t c0 = (uint32_t)r0[n], c1 = (uint32_t)r1[n];
-      const int i = 4 * (t >> 3) + (t & 3), m = (t & 7) >> 2;       // word of the column group, token half
-      if constexpr (KB == 1) {
-        hi[i] |= (c0 | (c1 << 16)) << (8 * (j & 1) + 2 * q + m);      // the code is the plane's bit
-      } else if constexpr (KB == 4) {
-        w[16 * m + i] |= (c0 | (c1 << 16)) << (4 * q);                // chunk m, field ks
-      } else {
-        w[i] |= ((c0 & 3u) | ((c1 & 3u) << 16)) << (2 * q + 8 * m);   // slot ks + 4*m
-        if constexpr (KB == 3) hi[i] |= ((c0 >> 2) | ((c1 >> 2) << 16)) << (8 * (j & 1) + 2 * q + m);
-      }
+        const int t = t0 + n;
+        // the two codes side by side: the low halves of the biased codes are the codes
+        const uint32_t pair = __builtin_amdgcn_perm(b1[n], b0[n], 0x05040100u);
+        const int i = 4 * (t >> 3) + (t & 3), m = (t & 7) >> 2;       // word of the column group, token half
+        if constexpr (KB == 1) {
+          hi[i] |= pair << (8 * (j & 1) + 2 * q + m);                  // the code is the plane's bit
+        } else if constexpr (KB == 4) {
+          w[16 * m + i] |= pair << (4 * q);                            // chunk m, field ks
+        } else {
+          w[i] |= (pair & 0x00030003u) << (2 * q + 8 * m);             // slot ks + 4*m
+          if constexpr (KB == 3) hi[i] |= ((pair >> 2) & 0x00010001u) << (8 * (j & 1) + 2 * q + m);
+        }
       }
     }
 #pragma unroll
@@ -276,35 +295,45 @@ __global__ __launch_bounds__(128) void quantize_pack_kernel(QuantArgs a) {
     for (int hh = 0; hh < 2; hh++)
 #pragma unroll
       for (int e0 = 0; e0 < 32; e0 += 8) {
-      float r[8];
-      bool near = false;
-#pragma unroll
-      for (int n = 0; n < 8; n++) {
-        const uint32_t wv = xr[hh][e0 >> 3][n >> 1];
-        r[n] = quantize_fast<VB>((n & 1) ? half_hi(wv) : half_lo(wv), gp[hh], e0 + n, near);
-      }
-      if (near) {
+        uint32_t bc[8];                               // biased codes
+        bool near = gp[hh].slow;
 #pragma unroll
         for (int n = 0; n < 8; n++) {
-          const uint32_t wv = xr[hh][e0 >> 3][n >> 1];
-          r[n] = quantize_exact<VB>((n & 1) ? half_hi(wv) : half_lo(wv), gp[hh], e0 + n);
+          const half2_t xv = as_half2(xr[hh][e0 >> 3][n >> 1]);
+          bc[n] = quantize_fast<VB>(diff(xv[n & 1], gp[hh].mn), gp[hh], e0 + n, near);
         }
-      }
+        if (near) {
 #pragma unroll
-      for (int n = 0; n < 8; n++) {
-        const int e = e0 + n;
-        const uint32_t c = (uint32_t)r[n];
-        const int i = e & 15, sp = e >> 4;
-        if constexpr (VB == 1) {
-          ph[i] |= c << (16 * hh + 2 * sp);
-        } else if constexpr (VB == 4) {
-          pw[i] |= c << (16 * hh + 4 * sp);
-        } else {
-          pw[i] |= (c & 3u) << (16 * hh + 2 * sp);
-          if constexpr (VB == 3) ph[i] |= (c >> 2) << (16 * hh + 2 * sp);
+          for (int n = 0; n < 8; n++) {
+            const half2_t xv = as_half2(xr[hh][e0 >> 3][n >> 1]);
+            bc[n] = quantize_exact<VB>(diff(xv[n & 1], gp[hh].mn), gp[hh], e0 + n);
+          }
+        }
+#pragma unroll
+        for (int n = 0; n < 8; n++) {
+          const int e = e0 + n;
+          const int i = e & 15, sp = e >> 4;
+          // fields never overflow, so the shifted biased codes are added up and the bias taken off afterwards
+          if constexpr (VB == 1) {
+            ph[i] += bc[n] << (16 * hh + 2 * sp);
+          } else if constexpr (VB == 4) {
+            pw[i] += bc[n] << (16 * hh + 4 * sp);
+          } else if constexpr (VB == 2) {
+            pw[i] += bc[n] << (16 * hh + 2 * sp);
+          } else {
+            pw[i] |= (bc[n] & 3u) << (16 * hh + 2 * sp);
+            ph[i] |= ((bc[n] >> 2) & 1u) << (16 * hh + 2 * sp);
+          }
         }
       }
+    if constexpr (VB != 3) {
+      constexpr int kField = VB == 4 ? 4 : 2;
+      constexpr uint32_t kBiasSum = (kBias << 0) + (kBias << kField) + (kBias << 16) + (kBias << (16 + kField));
+#pragma unroll
+      for (int i = 0; i < 16; i++) {
+        if constexpr (VB == 1) ph[i] -= kBiasSum; else pw[i] -= kBiasSum;
       }
+    }
     uint32_t w[acc_words<VB>()];
     if constexpr (VB == 4) {
       // slot 2*g + sp: chunk g/2, field 2*(g%2) + sp; the chunk's words are complete after the pair (g, g^1)
