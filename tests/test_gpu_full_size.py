@@ -107,3 +107,109 @@ def test_full_size_fused_steps(name, kb, vb, layer, steps):
     for (b, j, ku, vu, rc), u in zip(refs, units):                                   # the flushed tile, bit for bit
         nt = rc.n_q // 32
         assert np.array_equal(records[int(u), :nt].cpu().numpy().view(np.uint32), rc.packed[0, :nt]), f"tile records of unit {u}"
+
+
+def test_full_size_multi_query_shape():
+    """The multi-query row bench.py times (32 sequences, 72 query heads on one kv head, context 4088, 2/2 bit, nine
+    head blocks per unit in the library-chosen launch): sampled sequences against the oracle."""
+    import torch
+    import paper_2506_08018_amd as kv
+    from oracle.kvmix_ref import RefCache
+    c2 = synth.CONFIGS["cfg2_llama2_7b"]
+    T, W = c2["T"], c2["W"]
+    B, Hq, Hkv = 32, 72, 1
+    n_w, n_q = W + 24, T - 8 - (W + 24)
+    shape, cfg = kv.Shape(B, Hq, Hkv), kv.LayerCfg(2, 2, W)
+    print("case multi-query 32 x 72 heads on 1 kv head", flush=True)
+    q, k, v = synth.gen_layer_torch("cuda", synth.BASE_SEED, 100, B, Hq, Hkv, n_q + n_w)
+    gc = kv.LayerCache(shape, cfg, T + synth.GEN_ROOM, W + 32)
+    kv.quantize_pack(shape, cfg, k[:, :, :n_q], v[:, :, :n_q], gc)
+    gc.set_window(k[:, :, n_q:], v[:, :, n_q:])
+    ws = torch.zeros(kv.workspace_bytes(shape, T + synth.GEN_ROOM), dtype=torch.uint8, device="cuda")
+    out = torch.zeros_like(q)
+    kv.decode_attn(shape, cfg, q, gc, out, ws)
+    torch.cuda.synchronize()
+    for b in np.random.default_rng(17).choice(B, 4, replace=False):
+        b = int(b)
+        ku, vu = t16(k[b, 0]).reshape(1, 1, -1, 128), t16(v[b, 0]).reshape(1, 1, -1, 128)
+        rc = RefCache(1, Hq, 1, 2, 2, W, T + synth.GEN_ROOM, W + 32)
+        assert rc.quantize_pack(ku[:, :, :n_q], vu[:, :, :n_q]) == 0
+        rc.set_window(ku[:, :, n_q:], vu[:, :, n_q:])
+        st, want = rc.decode_attn(t16(q[b]).reshape(1, Hq, 128))
+        assert st == 0
+        assert_attn_close(t16(out[b]).reshape(1, Hq, 128), want, f"multi-query sequence {b}", tight=True, tight_abs=2.5e-4)
+
+
+def test_full_size_chunk_append():
+    """The 4096-token chunk bench.py sends through kvmix_append_tokens at the headline shape (two launches): the
+    records of sampled units bit for bit, the window rows and the counts against token-by-token appends of the oracle."""
+    import torch
+    import paper_2506_08018_amd as kv
+    from oracle.kvmix_ref import RefCache
+    c2 = synth.CONFIGS["cfg2_llama2_7b"]
+    B, Hq, Hkv, W = c2["B"], c2["Hq"], c2["Hkv"], c2["W"]
+    n_chunk = 4096
+    shape, cfg = kv.Shape(B, Hq, Hkv), kv.LayerCfg(2, 2, W)
+    print("case 4096-token chunk append", flush=True)
+    _, k, v = synth.gen_layer_torch("cuda", synth.BASE_SEED, 200, B, Hq, Hkv, n_chunk)
+    gc = kv.LayerCache(shape, cfg, 2 * n_chunk + 64, W + 32)
+    kv.append_tokens(shape, cfg, k, v, gc)
+    torch.cuda.synchronize()
+    tiles = (2 * n_chunk + 64) // 32
+    records = gc.packed.view(torch.int32).view(B * Hkv, tiles, -1)
+    for u in np.random.default_rng(19).choice(B * Hkv, 3, replace=False):
+        b, j = divmod(int(u), Hkv)
+        ku, vu = t16(k[b, j]).reshape(1, 1, -1, 128), t16(v[b, j]).reshape(1, 1, -1, 128)
+        rc = RefCache(1, 1, 1, 2, 2, W, 2 * n_chunk + 64, W + 32)
+        for t in range(n_chunk):
+            assert rc.append(ku[:, :, t], vu[:, :, t]) == 0
+        assert (gc.n_q, gc.n_w, gc.w0) == (rc.n_q, rc.n_w, rc.w0)
+        nt = rc.n_q // 32
+        assert np.array_equal(records[int(u), :nt].cpu().numpy().view(np.uint32), rc.packed[0, :nt]), f"tile records of unit {u}"
+        gk = t16(gc.k_win.view(torch.float16).view(B * Hkv, W + 32, 128)[int(u)])
+        gv = t16(gc.v_win.view(torch.float16).view(B * Hkv, W + 32, 128)[int(u)])
+        for i in range(rc.n_w):
+            slot = (rc.w0 + i) % (W + 32)
+            assert np.array_equal(gk[slot], rc.k_win[0, slot]) and np.array_equal(gv[slot], rc.v_win[0, slot]), f"window slot {slot} of unit {u}"
+
+
+def test_full_size_fronts_apart():
+    """The row bench.py times with the Value front ahead of the Key front (ratios 0.2 / 0.1 of Sec. 3.3 at the headline
+    shape, 3/2 bit, two launches per call): sampled units against the oracle taken through the same calls."""
+    import torch
+    import paper_2506_08018_amd as kv
+    from oracle.kvmix_ref import RefCache
+    c2 = synth.CONFIGS["cfg2_llama2_7b"]
+    B, Hq, Hkv, T = c2["B"], c2["Hq"], c2["Hkv"], c2["T"]
+    G = Hq // Hkv
+    Wc = 1024
+    shape, cfg = kv.Shape(B, Hq, Hkv), kv.LayerCfg(3, 2, -1)
+    print("case fronts apart at the headline shape", flush=True)
+    q, k, v = synth.gen_layer_torch("cuda", synth.BASE_SEED, 300, B, Hq, Hkv, T)
+    gc = kv.LayerCache(shape, cfg, T + synth.GEN_ROOM, Wc)
+    head_len = T - Wc + 32
+    kv.quantize_pack(shape, cfg, k[:, :, :head_len], v[:, :, :head_len], gc)
+    kv.append_tokens(shape, cfg, k[:, :, head_len:], v[:, :, head_len:], gc)
+    keep_k, keep_v = kv.rpc_next(0.2, 0.1, T, T)
+    kv.flush(shape, cfg, gc, keep_k, keep_v)
+    ws = torch.zeros(kv.workspace_bytes(shape, T + synth.GEN_ROOM), dtype=torch.uint8, device="cuda")
+    out = torch.zeros_like(q)
+    kv.decode_attn(shape, cfg, q, gc, out, ws)
+    torch.cuda.synchronize()
+    assert gc.v_lead > 0 and gc.n_q + gc.v_lead < T
+    tiles = (T + synth.GEN_ROOM) // 32
+    records = gc.packed.view(torch.int32).view(B * Hkv, tiles, -1)
+    for u in np.random.default_rng(23).choice(B * Hkv, 4, replace=False):
+        b, j = divmod(int(u), Hkv)
+        ku, vu = t16(k[b, j]).reshape(1, 1, -1, 128), t16(v[b, j]).reshape(1, 1, -1, 128)
+        rc = RefCache(1, G, 1, 3, 2, -1, T + synth.GEN_ROOM, Wc)
+        assert rc.quantize_pack(ku[:, :, :head_len], vu[:, :, :head_len]) == 0
+        for t in range(head_len, T):
+            assert rc.append(ku[:, :, t], vu[:, :, t]) == 0
+        assert rc.flush(keep_k, keep_v) == 0
+        assert (gc.n_q, gc.n_w, gc.w0, gc.v_lead) == (rc.n_q, rc.n_w, rc.w0, rc.v_lead)
+        nt = rc.n_q // 32                                   # tiles below both fronts: whole records, bit for bit
+        assert np.array_equal(records[int(u), :nt].cpu().numpy().view(np.uint32), rc.packed[0, :nt]), f"tile records of unit {u}"
+        st, want = rc.decode_attn(t16(q[b, j * G:(j + 1) * G]).reshape(1, G, 128))
+        assert st == 0
+        assert_attn_close(t16(out[b, j * G:(j + 1) * G]).reshape(1, G, 128), want, f"fronts apart unit {u}", tight=True, tight_abs=2.5e-4)
