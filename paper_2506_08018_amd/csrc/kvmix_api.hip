@@ -300,13 +300,17 @@ int plan_attention(const kvmix_shape* sh, const kvmix_layer_cfg* cfg, const uint
     const int ou = out_units(sh);
     int s_max = n_items / 8;
     if (s_max > max_splits(sh)) s_max = max_splits(sh);
-    double best = 0.0;
+    double best = 0.0, unsplit = 0.0;
     n_splits = 1;
     for (int s = 1; s <= s_max || s == 1; s++) {
       const double rounds = (double)(((long long)ou * s + cus - 1) / cus);
       const double cost = rounds * (48.0 + (double)n_items / s);
+      if (s == 1) unsplit = cost;
       if (s == 1 || cost < best) { best = cost; n_splits = s; }
     }
+    // an unsplit launch has no partials to write and merge, which the model leaves out: it wins a near tie
+    // (multi-query shape with 288 workgroups: 51 us unsplit, 55 us with 2 splits, modelled 352 against 336)
+    if (unsplit <= 1.06 * best) n_splits = 1;
   }
   if (n_splits > n_items) n_splits = n_items;
   AttnArgs a{};
