@@ -404,62 +404,46 @@ __global__ __launch_bounds__(768) void stream_read_kernel(const u32x4_t* buf, si
   if ((acc[0] & acc[1] & acc[2] & acc[3]) == 0xFFFFFFFFu && sink) sink[0] = 1u;
 }
 
-template <int KB, int VB, bool PARTIAL = false>
+template <int KB, int VB, bool PARTIAL>
 hipError_t launch_qp(const QuantArgs& a, dim3 grid, hipStream_t s) {
   quantize_pack_kernel<KB, VB, PARTIAL><<<grid, 128, 0, s>>>(a);
   return hipGetLastError();
 }
 
-}  // namespace
-
-hipError_t launch_quantize_pack(const QuantArgs& a, int k_bits, int v_bits,
-                                int n_tiles, int units, hipStream_t s) {
+// The bit pairs the library accepts: every pair of 1..4 (a 16-bit side never reaches the quantizer).
+template <bool PARTIAL>
+hipError_t launch_bits(const QuantArgs& a, int k_bits, int v_bits, int n_tiles, int units, hipStream_t s) {
   if (n_tiles == 0 || units == 0) return hipSuccess;
   const dim3 grid(n_tiles, a.Hkv, units / a.Hkv);
   switch (k_bits * 10 + v_bits) {
-    case 11: return launch_qp<1, 1>(a, grid, s);
-    case 12: return launch_qp<1, 2>(a, grid, s);
-    case 13: return launch_qp<1, 3>(a, grid, s);
-    case 14: return launch_qp<1, 4>(a, grid, s);
-    case 21: return launch_qp<2, 1>(a, grid, s);
-    case 31: return launch_qp<3, 1>(a, grid, s);
-    case 41: return launch_qp<4, 1>(a, grid, s);
-    case 22: return launch_qp<2, 2>(a, grid, s);
-    case 23: return launch_qp<2, 3>(a, grid, s);
-    case 24: return launch_qp<2, 4>(a, grid, s);
-    case 32: return launch_qp<3, 2>(a, grid, s);
-    case 33: return launch_qp<3, 3>(a, grid, s);
-    case 34: return launch_qp<3, 4>(a, grid, s);
-    case 42: return launch_qp<4, 2>(a, grid, s);
-    case 43: return launch_qp<4, 3>(a, grid, s);
-    case 44: return launch_qp<4, 4>(a, grid, s);
+    case 11: return launch_qp<1, 1, PARTIAL>(a, grid, s);
+    case 12: return launch_qp<1, 2, PARTIAL>(a, grid, s);
+    case 13: return launch_qp<1, 3, PARTIAL>(a, grid, s);
+    case 14: return launch_qp<1, 4, PARTIAL>(a, grid, s);
+    case 21: return launch_qp<2, 1, PARTIAL>(a, grid, s);
+    case 22: return launch_qp<2, 2, PARTIAL>(a, grid, s);
+    case 23: return launch_qp<2, 3, PARTIAL>(a, grid, s);
+    case 24: return launch_qp<2, 4, PARTIAL>(a, grid, s);
+    case 31: return launch_qp<3, 1, PARTIAL>(a, grid, s);
+    case 32: return launch_qp<3, 2, PARTIAL>(a, grid, s);
+    case 33: return launch_qp<3, 3, PARTIAL>(a, grid, s);
+    case 34: return launch_qp<3, 4, PARTIAL>(a, grid, s);
+    case 41: return launch_qp<4, 1, PARTIAL>(a, grid, s);
+    case 42: return launch_qp<4, 2, PARTIAL>(a, grid, s);
+    case 43: return launch_qp<4, 3, PARTIAL>(a, grid, s);
+    case 44: return launch_qp<4, 4, PARTIAL>(a, grid, s);
   }
   return hipErrorInvalidValue;
 }
 
-hipError_t launch_quantize_fronts(const QuantArgs& a, int k_bits, int v_bits,
-                                  int n_tiles, int units, hipStream_t s) {
-  if (n_tiles == 0 || units == 0) return hipSuccess;
-  const dim3 grid(n_tiles, a.Hkv, units / a.Hkv);
-  switch (k_bits * 10 + v_bits) {
-    case 11: return launch_qp<1, 1, true>(a, grid, s);
-    case 12: return launch_qp<1, 2, true>(a, grid, s);
-    case 13: return launch_qp<1, 3, true>(a, grid, s);
-    case 14: return launch_qp<1, 4, true>(a, grid, s);
-    case 21: return launch_qp<2, 1, true>(a, grid, s);
-    case 31: return launch_qp<3, 1, true>(a, grid, s);
-    case 41: return launch_qp<4, 1, true>(a, grid, s);
-    case 22: return launch_qp<2, 2, true>(a, grid, s);
-    case 23: return launch_qp<2, 3, true>(a, grid, s);
-    case 24: return launch_qp<2, 4, true>(a, grid, s);
-    case 32: return launch_qp<3, 2, true>(a, grid, s);
-    case 33: return launch_qp<3, 3, true>(a, grid, s);
-    case 34: return launch_qp<3, 4, true>(a, grid, s);
-    case 42: return launch_qp<4, 2, true>(a, grid, s);
-    case 43: return launch_qp<4, 3, true>(a, grid, s);
-    case 44: return launch_qp<4, 4, true>(a, grid, s);
-  }
-  return hipErrorInvalidValue;
+}  // namespace
+
+hipError_t launch_quantize_pack(const QuantArgs& a, int k_bits, int v_bits, int n_tiles, int units, hipStream_t s) {
+  return launch_bits<false>(a, k_bits, v_bits, n_tiles, units, s);
+}
+
+hipError_t launch_quantize_fronts(const QuantArgs& a, int k_bits, int v_bits, int n_tiles, int units, hipStream_t s) {
+  return launch_bits<true>(a, k_bits, v_bits, n_tiles, units, s);
 }
 
 hipError_t launch_dequant(const DequantArgs& a, int units, hipStream_t s) {
