@@ -46,6 +46,53 @@ def test_quantize_pack_adversarial_groups(kb, vb):
     assert_cache_equal(rc, gc)
 
 
+def near_tie_groups(rng, n_groups, q_max):
+    """Groups of 32 fp16 values [mn, mx, x ...] whose quotients (x - mn) / s (s = the group's stored step) lie within
+    a few 10^-6 relative of k + 1/2 without being ties: inside and just outside the band in which a kernel that
+    brackets the quotient has to fall back on the division. A minimum of small magnitude next to a range of order
+    one gives x - mn a fine grid, so such quotients exist (about one per group among all fp16 x).
+    (Inputs only: the expected codes come from the oracle.) Returns the groups and the number of near-tie elements."""
+    out = np.zeros((n_groups, 32), np.float16)
+    pos = np.arange(1, 0x7C00, dtype=np.uint16).view(np.float16)              # every positive finite fp16 number
+    n_near = 0
+    for g in range(n_groups):
+        mn = np.float16(rng.uniform(-1.0, 1.0) * 2.0 ** rng.integers(-12, -6))
+        mx = np.float16(rng.uniform(0.25, 16.0))
+        rng32 = np.float32(mx) - np.float32(mn)
+        s = np.float64(np.float16(rng32 / np.float32(q_max)))
+        x = pos[pos < mx]
+        d32 = (x.astype(np.float32) - np.float32(mn)).astype(np.float64)
+        t = d32 / s
+        d = np.abs(t - np.floor(t) - 0.5)
+        near = x[(d > 0) & (d < 8e-6 * np.maximum(t, 1.0)) & (t < q_max + 0.4)]
+        pick = rng.permutation(near)[:30]
+        n_near += len(pick)
+        fill = rng.choice(x, 30 - len(pick)) if len(pick) < 30 else np.zeros(0, np.float16)
+        out[g] = np.concatenate([[mn, mx], pick, fill]).astype(np.float16)
+    return out, n_near
+
+
+@pytest.mark.parametrize("bits", [1, 2, 3, 4])
+def test_quantize_pack_near_tie_quotients(bits):
+    print(f"case near-tie quotients bits={bits}", flush=True)
+    B, Hkv, T = 1, 2, 128
+    rng = np.random.default_rng(40 + bits)
+    q_max = (1 << bits) - 1
+    vg, n_v = near_tie_groups(rng, B * Hkv * T * 4, q_max)
+    vg = vg.reshape(B, Hkv, T, 4, 32)
+    v = vg.reshape(B, Hkv, T, 128)                                           # Values: a group is 32 channels of a token
+    kg, n_k = near_tie_groups(rng, B * Hkv * (T // 32) * 128, q_max)
+    kg = kg.reshape(B, Hkv, T // 32, 128, 32)
+    assert n_v > 50 and n_k > 50, (n_v, n_k)      # the inputs do hold such quotients
+    k = np.ascontiguousarray(kg.transpose(0, 1, 2, 4, 3)).reshape(B, Hkv, T, 128)   # Keys: 32 tokens of a channel
+    q = np.zeros((B, Hkv, 128), np.float16)
+    pad_k, pad_v = k[:, :, :32], v[:, :, :32]                                 # the window tokens make_pair leaves unpacked
+    _, _, _, rc, gc, shape, cfg = make_pair(B, Hkv, Hkv, T + 32, 32, bits, bits,
+                                            q_k_v=(q, np.concatenate([k, pad_k], 2), np.concatenate([v, pad_v], 2)))
+    assert gc.n_q == rc.n_q == T
+    assert_cache_equal(rc, gc)
+
+
 def test_quantize_pack_offsets_and_strides():
     """Writing at a token offset into a larger cache, from a strided (sliced) source."""
     import torch
